@@ -1,0 +1,281 @@
+/*
+ * CPU oracle (test infrastructure) -- see s4c_oracle.h.  Plain loops, double arithmetic,
+ * no blocking or fusion; OpenMP only spreads independent (sequence, head) / row units
+ * over the host cores.
+ */
+#include "s4c_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double load_elem(const void* base, int32_t dtype, size_t idx) {
+    if (dtype == 0) return (double)((const float*)base)[idx];
+    uint32_t bits = ((uint32_t)((const uint16_t*)base)[idx]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static size_t elem_size(int32_t dtype) { return dtype == 0 ? 4 : 2; }
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* -1 <= parent[i] < i for all i  */
+static int forest_ok(const int32_t* parent, int32_t N) {
+    for (int32_t i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return 0;
+    return 1;
+}
+
+/* One output vector: node i of sequence b, query head h.  Sec. 3.2 / Fig. 3: the visible
+ * set is the whole prefix plus the node's own root-to-node path. */
+static void attn_one(const oracle_shape* s, const void* q, const void* k_tree, const void* v_tree,
+                     const void* k_cache, const void* v_cache, int32_t clen, const int32_t* parent,
+                     double scale, int32_t b, int32_t i, int32_t h, double* out) {
+    const int32_t D = s->D, N = s->N, Hq = s->Hq, Hkv = s->Hkv;
+    const int32_t kvh = h / (Hq / Hkv);
+    const size_t qoff = (((size_t)b * N + i) * Hq + h) * D;
+
+    /* visible tree rows: i, parent[i], parent[parent[i]], ... */
+    int32_t anc[4096];
+    int32_t na = 0;
+    for (int32_t j = i; j >= 0; j = parent[j]) anc[na++] = j;
+
+    const int32_t nvis = clen + na;
+    double* sc = (double*)malloc(sizeof(double) * (size_t)(nvis > 0 ? nvis : 1));
+
+    for (int32_t t = 0; t < nvis; ++t) {
+        size_t koff;
+        const void* kb;
+        if (t < clen) {
+            kb = k_cache;
+            koff = (((size_t)b * Hkv + kvh) * s->S_cap + t) * D;
+        } else {
+            kb = k_tree;
+            koff = (((size_t)b * N + anc[t - clen]) * Hkv + kvh) * D;
+        }
+        double dot = 0.0;
+        for (int32_t d = 0; d < D; ++d) dot += load_elem(q, s->dtype, qoff + d) * load_elem(kb, s->dtype, koff + d);
+        sc[t] = dot * scale;
+    }
+    double mx = -INFINITY;
+    for (int32_t t = 0; t < nvis; ++t)
+        if (sc[t] > mx) mx = sc[t];
+    double denom = 0.0;
+    for (int32_t t = 0; t < nvis; ++t) {
+        sc[t] = exp(sc[t] - mx);
+        denom += sc[t];
+    }
+    for (int32_t d = 0; d < D; ++d) out[d] = 0.0;
+    for (int32_t t = 0; t < nvis; ++t) {
+        size_t voff;
+        const void* vb;
+        if (t < clen) {
+            vb = v_cache;
+            voff = (((size_t)b * Hkv + kvh) * s->S_cap + t) * D;
+        } else {
+            vb = v_tree;
+            voff = (((size_t)b * N + anc[t - clen]) * Hkv + kvh) * D;
+        }
+        const double w = sc[t] / denom;
+        for (int32_t d = 0; d < D; ++d) out[d] += w * load_elem(vb, s->dtype, voff + d);
+    }
+    free(sc);
+}
+
+int oracle_tree_attn(const oracle_shape* s, const void* q, const void* k_tree, const void* v_tree,
+                     const void* k_cache, const void* v_cache, const int32_t* cache_len,
+                     const int32_t* parent, double scale, double* out, int32_t* status) {
+    if (s->N > 4096) return -1;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)s->D);
+    const int32_t B = s->B, N = s->N, Hq = s->Hq, D = s->D;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t st = 0;
+        if (!forest_ok(parent + (size_t)b * N, N)) st |= ORACLE_BAD_TREE;
+        if (cache_len[b] < 0 || cache_len[b] > s->S_cap) st |= ORACLE_BAD_LEN;
+        if (status) status[b] = st;
+        if (st) {
+            memset(out + (size_t)b * N * Hq * D, 0, sizeof(double) * (size_t)N * Hq * D);
+            continue;
+        }
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+        for (int32_t h = 0; h < Hq; ++h)
+            for (int32_t i = 0; i < N; ++i)
+                attn_one(s, q, k_tree, v_tree, k_cache, v_cache, cache_len[b], parent + (size_t)b * N,
+                         scale, b, i, h, out + (((size_t)b * N + i) * Hq + h) * D);
+    }
+    return 0;
+}
+
+int oracle_tree_attn_sampled(const oracle_shape* s, const void* q, const void* k_tree,
+                             const void* v_tree, const void* k_cache, const void* v_cache,
+                             const int32_t* cache_len, const int32_t* parent, double scale,
+                             int32_t n, const int32_t* bnh, double* out) {
+    if (s->N > 4096) return -1;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)s->D);
+    for (int32_t b = 0; b < s->B; ++b) {
+        if (!forest_ok(parent + (size_t)b * s->N, s->N)) return -2;
+        if (cache_len[b] < 0 || cache_len[b] > s->S_cap) return -3;
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t t = 0; t < n; ++t) {
+        const int32_t b = bnh[3 * t], i = bnh[3 * t + 1], h = bnh[3 * t + 2];
+        attn_one(s, q, k_tree, v_tree, k_cache, v_cache, cache_len[b], parent + (size_t)b * s->N,
+                 scale, b, i, h, out + (size_t)t * s->D);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ acceptance */
+
+static void row_stats_one(const void* logits, int32_t dtype, size_t off, int32_t V, double T,
+                          int32_t* amax, double* rmax, double* sexp) {
+    int32_t g = 0;
+    double m = load_elem(logits, dtype, off);
+    for (int32_t v = 1; v < V; ++v) {
+        const double x = load_elem(logits, dtype, off + v);
+        if (x > m) { m = x; g = v; }          /* strict: ties keep the lowest index */
+    }
+    double sum = 0.0;
+    for (int32_t v = 0; v < V; ++v) sum += exp((load_elem(logits, dtype, off + v) - m) / T);
+    *amax = g;
+    *rmax = m;
+    *sexp = sum;
+}
+
+int oracle_row_stats(int32_t rows, int32_t V, int32_t dtype, double temperature,
+                     const void* logits, int32_t* argmax, double* rowmax, double* sumexp) {
+    if (temperature <= 0.0) temperature = 1.0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t r = 0; r < rows; ++r)
+        row_stats_one(logits, dtype, (size_t)r * V, V, temperature, &argmax[r], &rowmax[r], &sumexp[r]);
+    return 0;
+}
+
+int oracle_accept_path(int32_t B, int32_t N, int32_t V, int32_t dtype, int32_t mode,
+                       double temperature, const void* logits, const int32_t* parent,
+                       const int32_t* tokens, const float* p_draft, const float* uniforms,
+                       int32_t max_path, int32_t* path, int32_t* accept_len,
+                       int32_t* accepted_tokens, int32_t* bonus_token, double* margin,
+                       int32_t* status) {
+    if (N < 1 || max_path < 1) return -1;
+    if (mode == 1 && temperature <= 0.0) return -1;
+    if (mode == 0) temperature = 1.0;
+    int32_t* g = (int32_t*)malloc(sizeof(int32_t) * (size_t)B * N);
+    double* m = (double*)malloc(sizeof(double) * (size_t)B * N);
+    double* S = (double*)malloc(sizeof(double) * (size_t)B * N);
+    oracle_row_stats(B * N, V, dtype, temperature, logits, g, m, S);
+
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t* par = parent + (size_t)b * N;
+        const int32_t* tok = tokens + (size_t)b * N;
+        int32_t* pth = path + (size_t)b * max_path;
+        int32_t* atk = accepted_tokens + (size_t)b * max_path;
+        for (int32_t k = 0; k < max_path; ++k) { pth[k] = -1; atk[k] = -1; }
+        if (margin) margin[b] = INFINITY;
+
+        int32_t* depth = (int32_t*)malloc(sizeof(int32_t) * N);
+        char* acc = (char*)malloc(N);
+        int bad = (par[0] != -1);
+        for (int32_t i = 1; i < N && !bad; ++i)
+            if (par[i] < 0 || par[i] >= i) bad = 1;
+        if (!bad) {
+            depth[0] = 0;
+            for (int32_t i = 1; i < N; ++i) {
+                depth[i] = depth[par[i]] + 1;
+                if (depth[i] >= max_path) bad = 1;
+            }
+        }
+        if (bad) {
+            if (status) status[b] = ORACLE_BAD_TREE;
+            pth[0] = 0;
+            accept_len[b] = 0;
+            bonus_token[b] = -1;
+            free(depth);
+            free(acc);
+            continue;
+        }
+        if (status) status[b] = 0;
+
+        acc[0] = 1;
+        for (int32_t i = 1; i < N; ++i) {
+            const int32_t p = par[i];
+            int ok;
+            if (mode == 0) {
+                ok = (tok[i] == g[(size_t)b * N + p]);
+            } else if (tok[i] < 0 || tok[i] >= V) {
+                ok = 0;
+            } else {
+                const size_t r = (size_t)b * N + p;
+                const double lx = load_elem(logits, dtype, r * V + tok[i]);
+                const double pt = exp((lx - m[r]) / temperature) / S[r];      /* target prob of the draft token */
+                const double lhs = (double)uniforms[(size_t)b * N + i] * (double)p_draft[(size_t)b * N + i];
+                ok = (lhs < pt);                                               /* u < pt/pd, strict */
+                if (margin) {
+                    const double den = lhs > pt ? lhs : pt;
+                    const double mg = den > 0.0 ? fabs(lhs - pt) / den : 0.0;
+                    if (mg < margin[b]) margin[b] = mg;
+                }
+            }
+            acc[i] = (char)(ok && acc[p]);
+        }
+        int32_t best = 0;
+        for (int32_t i = 1; i < N; ++i)
+            if (acc[i] && depth[i] > depth[best]) best = i;     /* strict: lowest index among equal depth */
+        const int32_t L = depth[best];
+        int32_t node = best;
+        for (int32_t k = L; k >= 0; --k) { pth[k] = node; node = par[node]; }
+        for (int32_t k = 1; k <= L; ++k) atk[k - 1] = tok[pth[k]];
+        accept_len[b] = L;
+        bonus_token[b] = (mode == 0) ? g[(size_t)b * N + best] : -1;
+        free(depth);
+        free(acc);
+    }
+    free(g);
+    free(m);
+    free(S);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ compaction */
+
+int oracle_kv_compact(const oracle_shape* s, const void* k_tree, const void* v_tree,
+                      void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                      const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
+                      int32_t* status) {
+    const size_t es = elem_size(s->dtype);
+    const size_t row = (size_t)s->D * es;
+    for (int32_t b = 0; b < s->B; ++b) {
+        const int32_t L = accept_len[b];
+        const int32_t base = cache_len[b];
+        const int32_t* pth = path + (size_t)b * max_path;
+        if (dst_index)
+            for (int32_t k = 0; k < max_path; ++k) dst_index[(size_t)b * max_path + k] = -1;
+        int bad = (L < 0 || L >= max_path || base < 0 || (int64_t)base + L + 1 > s->S_cap);
+        for (int32_t k = 0; !bad && k <= L; ++k)
+            if (pth[k] < 0 || pth[k] >= s->N) bad = 1;
+        if (status) status[b] = bad ? ORACLE_BAD_LEN : 0;
+        if (bad) continue;
+        for (int32_t k = 0; k <= L; ++k) {
+            for (int32_t h = 0; h < s->Hkv; ++h) {
+                const size_t src = (((size_t)b * s->N + pth[k]) * s->Hkv + h) * row;
+                const size_t dst = (((size_t)b * s->Hkv + h) * s->S_cap + (size_t)(base + k)) * row;
+                memcpy((char*)k_cache + dst, (const char*)k_tree + src, row);
+                memcpy((char*)v_cache + dst, (const char*)v_tree + src, row);
+            }
+            if (dst_index) dst_index[(size_t)b * max_path + k] = base + k;
+        }
+        cache_len[b] = base + L + 1;
+    }
+    return 0;
+}

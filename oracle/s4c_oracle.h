@@ -1,0 +1,91 @@
+/*
+ * CPU oracle for the tree-verification step of the continuous verification tree
+ * (paper Sec. 3.2, Fig. 3; acceptance rule: the unnumbered equation
+ * "r < min(1, q(x)/p(x))" of Sec. 3.2 and the speculative-sampling paragraph of Sec. 2).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, definition-level implementation in
+ * double precision.  It shares no code with the HIP library and must never be called from
+ * the product path; only tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * Every pointer is a HOST pointer.  dtype: 0 = fp32, 1 = bf16 stored as uint16 bit patterns.
+ * Layouts (row-major, innermost last):
+ *   q, out       [B][N][Hq][D]        k_tree, v_tree [B][N][Hkv][D]
+ *   k_cache, v_cache [B][Hkv][S_cap][D]   cache_len [B]   parent [B][N]
+ *   logits [B][N][V]   tokens, p_draft, uniforms [B][N]
+ * Query head h reads KV head h / (Hq/Hkv).
+ *
+ * Parity pins (tests, CPU only): brute-force per-node sequential causal attention on tiny
+ * trees, chain tree == ordinary causal attention (library routine), closed forms (equal
+ * keys -> mean of visible values, V == 1 -> output 1, empty prefix root -> V_root),
+ * hand-worked acceptance examples, chain == sequential speculative-sampling rule,
+ * compaction == appending accepted tokens one at a time.  Nothing here is unpinned.
+ */
+#ifndef S4C_ORACLE_H
+#define S4C_ORACLE_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t B, Hq, Hkv, D, N, S_cap, dtype;
+} oracle_shape;
+
+/* status bits written per sequence */
+#define ORACLE_BAD_TREE 1
+#define ORACLE_BAD_LEN  2
+
+/* Tree-masked attention, Sec. 3.2 / Fig. 3: node i sees cache rows [0, cache_len[b]) and the
+ * tree rows of i itself and of its ancestors.  out is double [B][N][Hq][D].  A sequence
+ * whose parent[] violates -1 <= parent[i] < i (status bit 1) or whose cache_len is outside
+ * [0, S_cap] (bit 2) gets an all-zero output.  scale <= 0 means 1/sqrt(D).  Returns 0. */
+int oracle_tree_attn(const oracle_shape* s, const void* q, const void* k_tree, const void* v_tree,
+                     const void* k_cache, const void* v_cache, const int32_t* cache_len,
+                     const int32_t* parent, double scale, double* out, int32_t* status);
+
+/* Same definition, evaluated only at n sampled (b, node, head) triples; out is [n][D]. */
+int oracle_tree_attn_sampled(const oracle_shape* s, const void* q, const void* k_tree,
+                             const void* v_tree, const void* k_cache, const void* v_cache,
+                             const int32_t* cache_len, const int32_t* parent, double scale,
+                             int32_t n, const int32_t* bnh, double* out);
+
+/* Acceptance + longest accepted path (Sec. 3.2).  mode 0 greedy: node i (i >= 1) passes iff
+ * tokens[i] equals the lowest-index argmax of logits row parent[i].  mode 1 stochastic: passes
+ * iff u[i] * p_draft[i] < softmax(logits[parent[i]] / T)[tokens[i]]  (strict).  A node is
+ * accepted iff it passes and its parent is accepted; the root always is.  The result is the
+ * accepted node of greatest depth (lowest index among equals) and the path root..node.
+ *   path [B][max_path] (-1 padded), accept_len [B] = path nodes - 1,
+ *   accepted_tokens [B][max_path] = tokens of path[1..] (-1 padded),
+ *   bonus_token [B] = greedy: argmax of the last path node's row; stochastic: -1,
+ *   margin [B] (nullable) = min over tested nodes of |u*pd - pt| / max(u*pd, pt)
+ *                           (stochastic; +inf in greedy),
+ *   status [B] (nullable): bit 1 if parent[0] != -1 or parent[i] not in [0, i) or a path would
+ *                          exceed max_path; then accept_len = 0, path = [0], bonus = -1. */
+int oracle_accept_path(int32_t B, int32_t N, int32_t V, int32_t dtype, int32_t mode,
+                       double temperature, const void* logits, const int32_t* parent,
+                       const int32_t* tokens, const float* p_draft, const float* uniforms,
+                       int32_t max_path, int32_t* path, int32_t* accept_len,
+                       int32_t* accepted_tokens, int32_t* bonus_token, double* margin,
+                       int32_t* status);
+
+/* Row statistics used above, exposed for pins: lowest-index argmax, max, and
+ * sum_v exp((l_v - max)/T) in double. */
+int oracle_row_stats(int32_t rows, int32_t V, int32_t dtype, double temperature,
+                     const void* logits, int32_t* argmax, double* rowmax, double* sumexp);
+
+/* KV reuse (Sec. 3.2, last paragraph): for k = 0..accept_len[b], copy tree row path[b][k] of
+ * every KV head into cache row cache_len[b] + k, for K and V; then cache_len[b] += accept_len+1.
+ * dst_index [B][max_path] (nullable) receives the cache row written for path[k], -1 padded.
+ * A sequence whose rows would not fit S_cap or whose path is malformed is left untouched
+ * (status bit 2). */
+int oracle_kv_compact(const oracle_shape* s, const void* k_tree, const void* v_tree,
+                      void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                      const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
+                      int32_t* status);
+
+int oracle_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,151 @@
+"""ctypes wrapper of the CPU oracle (TEST INFRASTRUCTURE -- never used by the product path).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
+It compiles ``s4c_oracle.c`` with gcc on first use and marshals numpy arrays; all of the
+arithmetic lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "s4c_oracle.c")
+_LIB = os.path.join(_HERE, "libs4c_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "s4c_oracle.h"))):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "N", "S_cap", "dtype")]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    raise TypeError("oracle arrays must be float32 or uint16 (bf16 bits), got %s" % a.dtype)
+
+
+def _p(a):
+    if a is None:
+        return C.c_void_p(0)
+    assert a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a
+
+
+def _shape(q, k_tree, k_cache):
+    B, N, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    S_cap = k_cache.shape[2]
+    assert k_tree.shape == (B, N, Hkv, D) and k_cache.shape == (B, Hkv, S_cap, D)
+    return _Shape(B, Hq, Hkv, D, N, S_cap, _dt(q))
+
+
+def tree_attn(q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, scale=0.0):
+    """-> (out float64 [B][N][Hq][D], status int32 [B])"""
+    lib = _load()
+    s = _shape(q, k_tree, k_cache)
+    cache_len, parent = _i32(cache_len), _i32(parent)
+    out = np.empty(q.shape, dtype=np.float64)
+    status = np.zeros(s.B, dtype=np.int32)
+    rc = lib.oracle_tree_attn(C.byref(s), _p(q), _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache),
+                              _p(cache_len), _p(parent), C.c_double(scale), _p(out), _p(status))
+    assert rc == 0
+    return out, status
+
+
+def tree_attn_sampled(q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, bnh, scale=0.0):
+    """bnh int32 [n][3] = (sequence, node, query head) -> out float64 [n][D]"""
+    lib = _load()
+    s = _shape(q, k_tree, k_cache)
+    cache_len, parent, bnh = _i32(cache_len), _i32(parent), _i32(bnh)
+    n = bnh.shape[0]
+    out = np.empty((n, s.D), dtype=np.float64)
+    rc = lib.oracle_tree_attn_sampled(C.byref(s), _p(q), _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache),
+                                      _p(cache_len), _p(parent), C.c_double(scale), C.c_int32(n), _p(bnh), _p(out))
+    assert rc == 0, rc
+    return out
+
+
+def row_stats(logits, temperature=1.0):
+    """logits [rows][V] -> (argmax int32, max float64, sumexp float64)"""
+    lib = _load()
+    rows, V = logits.shape
+    g = np.empty(rows, dtype=np.int32)
+    m = np.empty(rows, dtype=np.float64)
+    S = np.empty(rows, dtype=np.float64)
+    rc = lib.oracle_row_stats(C.c_int32(rows), C.c_int32(V), C.c_int32(_dt(logits)), C.c_double(temperature),
+                              _p(logits), _p(g), _p(m), _p(S))
+    assert rc == 0
+    return g, m, S
+
+
+def accept_path(logits, parent, tokens, mode, max_path, p_draft=None, uniforms=None, temperature=1.0):
+    """mode "greedy"|"stochastic" -> dict(path, accept_len, accepted_tokens, bonus_token, margin, status)"""
+    lib = _load()
+    B, N, V = logits.shape
+    parent, tokens = _i32(parent), _i32(tokens)
+    m = {"greedy": 0, "stochastic": 1}[mode]
+    if m == 1:
+        p_draft = np.ascontiguousarray(p_draft, dtype=np.float32)
+        uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+    path = np.empty((B, max_path), dtype=np.int32)
+    atok = np.empty((B, max_path), dtype=np.int32)
+    alen = np.empty(B, dtype=np.int32)
+    bonus = np.empty(B, dtype=np.int32)
+    margin = np.empty(B, dtype=np.float64)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_accept_path(C.c_int32(B), C.c_int32(N), C.c_int32(V), C.c_int32(_dt(logits)), C.c_int32(m),
+                                C.c_double(temperature), _p(logits), _p(parent), _p(tokens),
+                                _p(p_draft if m == 1 else None), _p(uniforms if m == 1 else None),
+                                C.c_int32(max_path), _p(path), _p(alen), _p(atok), _p(bonus), _p(margin), _p(status))
+    assert rc == 0, rc
+    return dict(path=path, accept_len=alen, accepted_tokens=atok, bonus_token=bonus, margin=margin, status=status)
+
+
+def kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len):
+    """In place on k_cache, v_cache, cache_len (numpy arrays) -> (dst_index, status)"""
+    lib = _load()
+    B, N, Hkv, D = k_tree.shape
+    S_cap = k_cache.shape[2]
+    s = _Shape(B, Hkv, Hkv, D, N, S_cap, _dt(k_tree))
+    assert cache_len.dtype == np.int32 and cache_len.flags["C_CONTIGUOUS"]
+    path, accept_len = _i32(path), _i32(accept_len)
+    max_path = path.shape[1]
+    dst = np.empty((B, max_path), dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_kv_compact(C.byref(s), _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache), _p(cache_len),
+                               _p(path), _p(accept_len), C.c_int32(max_path), _p(dst), _p(status))
+    assert rc == 0
+    return dst, status
