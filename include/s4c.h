@@ -1,0 +1,137 @@
+/*
+ * s4c.h -- C ABI of the MI355X (gfx950) tree-verification library.
+ *
+ * One verification step of the continuous verification tree (paper Sec. 3.2, Fig. 3):
+ *   1. s4c_tree_attn    every drafted node is scored in one pass; a node attends to the shared
+ *                       prefix KV cache plus only itself and its ancestors (the tree mask);
+ *   2. s4c_accept_path  per-node acceptance (greedy, or the stochastic rule r < min(1, q/p)
+ *                       of Sec. 3.2) and the longest accepted root-to-node path;
+ *   3. s4c_kv_compact   the accepted path's K/V rows are appended to the cache so the next
+ *                       round reuses them (last paragraph of Sec. 3.2).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller; `shape` structs are HOST
+ *     pointers.  The library allocates nothing and keeps no state.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t, may be NULL for the default
+ *     stream) and never synchronise; they may be chained on one stream
+ *     (s4c_accept_path -> s4c_kv_compact reads `path` on the device).
+ *   - The return value reports what the host can check (null pointer, shape, unsupported
+ *     size, workspace too small, launch failure).  Data-dependent problems (malformed
+ *     parent[], cache_len out of range) are reported per sequence in a device `status` word
+ *     and the affected sequence gets a defined result, never undefined behaviour.
+ *   - Inputs are not modified except k_cache / v_cache / cache_len in s4c_kv_compact.
+ *   - Row-major layouts, innermost dimension last.  dtype selects the element type of
+ *     Q/K/V/cache/out (and of logits): fp32, or bf16 with fp32 accumulation.
+ *   - Limits: 1 <= N <= 128, D in {64, 128}, Hq % Hkv == 0.
+ */
+#ifndef S4C_H
+#define S4C_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    S4C_OK = 0,
+    S4C_ERR_NULL = -1,         /* a required pointer is NULL */
+    S4C_ERR_SHAPE = -2,        /* non-positive or inconsistent sizes */
+    S4C_ERR_UNSUPPORTED = -3,  /* N > 128, D not in {64,128}, unknown dtype or mode */
+    S4C_ERR_WORKSPACE = -4,    /* workspace missing or smaller than *_workspace_size() */
+    S4C_ERR_HIP = -5           /* kernel launch failed (hipGetLastError) */
+} s4c_status;
+
+typedef enum { S4C_F32 = 0, S4C_BF16 = 1 } s4c_dtype;
+typedef enum { S4C_GREEDY = 0, S4C_STOCHASTIC = 1 } s4c_accept_mode;
+
+/* bits of the per-sequence device status word */
+#define S4C_SEQ_BAD_TREE 1     /* parent[] is not a valid tree / path deeper than max_path */
+#define S4C_SEQ_BAD_LEN  2     /* cache_len out of range / accepted rows do not fit S_cap */
+
+typedef struct {
+    int32_t B;       /* sequences */
+    int32_t Hq;      /* query heads */
+    int32_t Hkv;     /* KV heads; query head h reads KV head h / (Hq/Hkv) */
+    int32_t D;       /* head size */
+    int32_t N;       /* tree nodes including the root (node 0 = last committed token) */
+    int32_t S_cap;   /* row capacity of the KV cache per (sequence, KV head) */
+    int32_t dtype;   /* s4c_dtype */
+} s4c_attn_shape;
+
+/* Bytes of device workspace s4c_tree_attn needs for this shape when no sequence's cache_len
+ * exceeds max_cache_len (0 if the shape is invalid).  May be 0 (single pass, no partials). */
+size_t s4c_tree_attn_workspace_size(const s4c_attn_shape* shape, int32_t max_cache_len);
+
+/* Tree-masked attention (Sec. 3.2, Fig. 3 mask matrix).  For sequence b, node i, query head h:
+ *   out[b][i][h] = sum_j softmax_j(scale * q[b][i][h] . k_j) v_j
+ * over j in { cache rows 0 .. cache_len[b]-1 of KV head h/G } U { tree rows of node i and of
+ * its ancestors }.  Accumulation and softmax are fp32.
+ *   q, out          [B][N][Hq][D]
+ *   k_tree, v_tree  [B][N][Hkv][D]      K/V of the tree nodes (not yet in the cache)
+ *   k_cache, v_cache [B][Hkv][S_cap][D]
+ *   cache_len       [B]   0 <= cache_len[b] <= min(max_cache_len, S_cap)
+ *   parent          [B][N] parent[b][0] = -1 and -1 <= parent[b][i] < i
+ *   max_cache_len   host-side upper bound of cache_len[] (sizes the launch)
+ *   scale           <= 0 selects 1/sqrt(D)
+ *   status          [B] nullable; receives S4C_SEQ_* bits (0 = fine).  A flagged sequence
+ *                   gets an all-zero output.
+ *   workspace       >= s4c_tree_attn_workspace_size(shape, max_cache_len) bytes, 256-byte
+ *                   aligned; contents need not be initialised; may be NULL if that size is 0.
+ * Results are deterministic (fixed split count and merge order for a given shape). */
+s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void* k_tree,
+                         const void* v_tree, const void* k_cache, const void* v_cache,
+                         const int32_t* cache_len, const int32_t* parent, int32_t max_cache_len,
+                         float scale, void* out, int32_t* status, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace s4c_accept_path needs (per-row partial statistics). */
+size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V);
+
+/* Acceptance and longest accepted path (Sec. 3.2).
+ *   logits  [B][N][V] (logits_dtype); row i is the target model's distribution for the token
+ *           that follows node i, i.e. it verifies the children of node i.
+ *   parent, tokens [B][N]; node 0 is the unique root (parent -1), 0 <= parent[i] < i.
+ *   GREEDY      node i >= 1 passes iff tokens[i] == argmax(logits[parent[i]]), ties in the
+ *               argmax resolved to the lowest token id (greedy decoding, Sec. 4.1.2).
+ *   STOCHASTIC  node i passes iff uniforms[i] * p_draft[i] < softmax(logits[parent[i]]/T)[tokens[i]]
+ *               (the test r < min(1, q(x)/p(x)) of Sec. 3.2 without the division; strict).
+ *               p_draft[i] = draft probability of tokens[i] given its parent; uniforms in [0,1);
+ *               both [B][N] fp32, entry 0 unused; NULL allowed in greedy mode.  T > 0.
+ *   A node is accepted iff it passes and its parent is accepted (the root always is).  The
+ *   result is the accepted node of greatest depth, lowest node index among equals.
+ *   max_path  row stride of path / accepted_tokens; must exceed the tree's greatest depth.
+ *   path            [B][max_path] node ids root..last, -1 padded
+ *   accept_len      [B] accepted draft tokens (= path nodes - 1)
+ *   accepted_tokens [B][max_path] tokens of path[1..], -1 padded
+ *   bonus_token     [B] greedy: argmax of the last path node's row; stochastic: -1
+ *   status          [B] nullable; S4C_SEQ_BAD_TREE if parent[] is malformed or a node is deeper
+ *                   than max_path-1: then accept_len = 0, path = [0], bonus = -1.
+ * Softmax statistics are fp32. */
+s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
+                           float temperature, const void* logits, const int32_t* parent,
+                           const int32_t* tokens, const float* p_draft, const float* uniforms,
+                           int32_t max_path, int32_t* path, int32_t* accept_len,
+                           int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* KV reuse (Sec. 3.2, last paragraph): for k = 0 .. accept_len[b], tree row path[b][k] of every
+ * KV head is copied to cache row cache_len[b] + k (K and V); then cache_len[b] += accept_len[b]+1.
+ * Only shape->B, Hkv, D, N, S_cap, dtype are used.
+ *   dst_index [B][max_path] nullable: cache row written for path[k], -1 padded
+ *   status    [B] nullable: S4C_SEQ_BAD_LEN if the rows do not fit S_cap or path/accept_len is
+ *             malformed; that sequence's cache and cache_len are left untouched. */
+s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const void* v_tree,
+                          void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                          const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
+                          int32_t* status, void* hip_stream);
+
+/* Static, never NULL. */
+const char* s4c_strerror(s4c_status code);
+
+/* Number of KV splits s4c_tree_attn uses for this shape (1 = single pass); for reporting. */
+int32_t s4c_tree_attn_num_splits(const s4c_attn_shape* shape, int32_t max_cache_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of libs4c.so: same names as the C ABI, argument marshalling only.
+
+Every step of the tree-verification path runs in the HIP kernels behind these calls; PyTorch
+supplies device memory and the stream.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libs4c.so")
+
+S4C_F32, S4C_BF16 = 0, 1
+S4C_GREEDY, S4C_STOCHASTIC = 0, 1
+S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
+
+EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
+           "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits")
+
+
+class S4CError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("libs4c: %s (status %d)" % (msg, code))
+        self.code = code
+
+
+class AttnShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "N", "S_cap", "dtype")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libs4c.so (built in-tree by ``__graft_entry__.build()``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build the HIP library first (python -c 'import __graft_entry__ as g; g.build()')"
+                % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        L.s4c_tree_attn_workspace_size.restype = C.c_size_t
+        L.s4c_tree_attn_workspace_size.argtypes = [C.POINTER(AttnShape), C.c_int32]
+        L.s4c_tree_attn_num_splits.restype = C.c_int32
+        L.s4c_tree_attn_num_splits.argtypes = [C.POINTER(AttnShape), C.c_int32]
+        L.s4c_tree_attn.restype = C.c_int
+        L.s4c_tree_attn.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 7 + [
+            C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.s4c_accept_path_workspace_size.restype = C.c_size_t
+        L.s4c_accept_path_workspace_size.argtypes = [C.c_int32] * 3
+        L.s4c_accept_path.restype = C.c_int
+        L.s4c_accept_path.argtypes = [C.c_int32] * 5 + [C.c_float] + [C.c_void_p] * 5 + [C.c_int32] + [
+            C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_kv_compact.restype = C.c_int
+        L.s4c_kv_compact.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 7 + [C.c_int32] + [C.c_void_p] * 3
+        L.s4c_strerror.restype = C.c_char_p
+        L.s4c_strerror.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def s4c_strerror(code: int) -> str:
+    return lib().s4c_strerror(code).decode()
+
+
+def _check(code: int):
+    if code != 0:
+        raise S4CError(code, s4c_strerror(code))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libs4c takes contiguous device tensors")
+    return t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return S4C_F32
+    if t.dtype == torch.bfloat16:
+        return S4C_BF16
+    raise TypeError("libs4c supports float32 and bfloat16, got %s" % t.dtype)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def attn_shape(q: torch.Tensor, k_tree: torch.Tensor, k_cache: torch.Tensor) -> AttnShape:
+    B, N, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    S_cap = k_cache.shape[2]
+    if tuple(k_tree.shape) != (B, N, Hkv, D) or tuple(k_cache.shape) != (B, Hkv, S_cap, D):
+        raise ValueError("inconsistent q / k_tree / k_cache shapes")
+    return AttnShape(B, Hq, Hkv, D, N, S_cap, _dtype_code(q))
+
+
+def s4c_tree_attn_workspace_size(shape: AttnShape, max_cache_len: int) -> int:
+    return int(lib().s4c_tree_attn_workspace_size(C.byref(shape), max_cache_len))
+
+
+def s4c_tree_attn_num_splits(shape: AttnShape, max_cache_len: int) -> int:
+    return int(lib().s4c_tree_attn_num_splits(C.byref(shape), max_cache_len))
+
+
+def s4c_tree_attn(q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, max_cache_len: int,
+                  out: torch.Tensor, scale: float = 0.0, status: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Tree-masked attention of all N nodes; writes and returns ``out`` ([B][N][Hq][D])."""
+    shape = attn_shape(q, k_tree, k_cache)
+    for t in (k_tree, v_tree, k_cache, v_cache, out):
+        if t.dtype != q.dtype:
+            raise TypeError("q/k/v/cache/out must share one dtype")
+    if v_tree.shape != k_tree.shape or v_cache.shape != k_cache.shape or out.shape != q.shape:
+        raise ValueError("inconsistent v / out shapes")
+    if cache_len.dtype != torch.int32 or parent.dtype != torch.int32 or tuple(parent.shape) != (shape.B, shape.N):
+        raise TypeError("cache_len [B] and parent [B][N] must be int32")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().s4c_tree_attn(C.byref(shape), _ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
+                               _ptr(cache_len), _ptr(parent), int(max_cache_len), float(scale), _ptr(out),
+                               _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+    return out
+
+
+def s4c_accept_path_workspace_size(B: int, N: int, V: int) -> int:
+    return int(lib().s4c_accept_path_workspace_size(B, N, V))
+
+
+def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, accept_len, accepted_tokens,
+                    bonus_token, workspace, p_draft=None, uniforms=None, temperature: float = 1.0,
+                    status: Optional[torch.Tensor] = None) -> None:
+    B, N, V = logits.shape
+    for t in (parent, tokens):
+        if t.dtype != torch.int32 or tuple(t.shape) != (B, N):
+            raise TypeError("parent / tokens must be int32 [B][N]")
+    if tuple(path.shape) != (B, max_path) or tuple(accepted_tokens.shape) != (B, max_path):
+        raise ValueError("path / accepted_tokens must be [B][max_path]")
+    for t in (path, accept_len, accepted_tokens, bonus_token):
+        if t.dtype != torch.int32:
+            raise TypeError("outputs must be int32")
+    for t in (p_draft, uniforms):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (B, N)):
+            raise TypeError("p_draft / uniforms must be float32 [B][N]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().s4c_accept_path(B, N, V, _dtype_code(logits), int(mode), float(temperature), _ptr(logits),
+                                 _ptr(parent), _ptr(tokens), _ptr(p_draft), _ptr(uniforms), int(max_path),
+                                 _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
+                                 _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+
+
+def s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len,
+                   dst_index: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> None:
+    B, N, Hkv, D = k_tree.shape
+    S_cap = k_cache.shape[2]
+    if tuple(k_cache.shape) != (B, Hkv, S_cap, D) or v_tree.shape != k_tree.shape or v_cache.shape != k_cache.shape:
+        raise ValueError("inconsistent shapes")
+    if cache_len.dtype != torch.int32 or path.dtype != torch.int32 or accept_len.dtype != torch.int32:
+        raise TypeError("cache_len / path / accept_len must be int32")
+    shape = AttnShape(B, Hkv, Hkv, D, N, S_cap, _dtype_code(k_tree))
+    _check(lib().s4c_kv_compact(C.byref(shape), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
+                                _ptr(cache_len), _ptr(path), _ptr(accept_len), int(path.shape[1]),
+                                _ptr(dst_index), _ptr(status), _stream()))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
+    """Device scratch of at least nbytes (256-byte aligned by the torch allocator)."""
+    if nbytes <= 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)

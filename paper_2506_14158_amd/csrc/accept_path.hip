@@ -1,0 +1,247 @@
+// Path acceptance (paper Sec. 3.2: per-node test, then the longest accepted path).
+//
+// Kernel 1 (row_stats): the HBM-bound part.  Each workgroup reads one chunk of one logits row
+// exactly once with 16-byte loads, keeps the values in registers, and reduces
+//   (max value, lowest index attaining it)   -- argmax, ties to the lowest token id
+//   sum exp2((x - chunk max) * log2(e)/T)    -- stochastic mode only
+// with wavefront shuffles, then across the 4 waves through LDS.
+// Kernel 2 (path): one workgroup per sequence combines the chunk statistics per row, applies
+// the per-node test against the parent's row, ANDs along each node's ancestor chain and picks
+// the deepest accepted node (lowest index among equals), writing the path root..node.
+#include "common.h"
+
+namespace s4c {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPerThread = 32;                       // logits per thread
+constexpr int kChunk = kThreads * kPerThread;        // logits per workgroup
+
+struct MaxIdx {
+    float v;
+    int32_t i;
+};
+
+__device__ __forceinline__ MaxIdx better(MaxIdx a, MaxIdx b) {
+    // larger value wins; equal values: lower index wins (never depends on reduction order)
+    const bool take_b = (b.v > a.v) || (b.v == a.v && b.i < a.i);
+    return take_b ? b : a;
+}
+
+__device__ __forceinline__ MaxIdx wave_best(MaxIdx x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        MaxIdx y;
+        y.v = __shfl_xor(x.v, off);
+        y.i = __shfl_xor(x.i, off);
+        x = better(x, y);
+    }
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+template <typename T> struct Vec16;   // 16-byte vector of T
+template <> struct Vec16<float> { static constexpr int n = 4; };
+template <> struct Vec16<bf16_t> { static constexpr int n = 8; };
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
+    constexpr int VN = Vec16<T>::n;
+    constexpr int NV = kPerThread / VN;               // 16-byte loads per thread
+    const int row = blockIdx.x / a.chunks, ch = blockIdx.x % a.chunks, tid = threadIdx.x;
+    const int V = a.V;
+    const T* base = (const T*)a.logits + (size_t)row * V;
+    const int c0 = ch * kChunk;
+    const int cend = min(V, c0 + kChunk);
+
+    float x[kPerThread];
+    int32_t idx0[NV];                                  // index of the first element of each vector
+    const bool vec_ok = ((((uintptr_t)base) & 15) == 0);
+    if (vec_ok) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int e0 = c0 + (j * kThreads + tid) * VN;
+            idx0[j] = e0;
+            if (e0 + VN <= cend) {
+                const uint4 raw = *(const uint4*)(base + e0);
+                if constexpr (VN == 4) {
+                    x[j * VN + 0] = __uint_as_float(raw.x);
+                    x[j * VN + 1] = __uint_as_float(raw.y);
+                    x[j * VN + 2] = __uint_as_float(raw.z);
+                    x[j * VN + 3] = __uint_as_float(raw.w);
+                } else {
+                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        x[j * VN + 2 * k] = __uint_as_float(w[k] << 16);
+                        x[j * VN + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < VN; ++k) x[j * VN + k] = (e0 + k < cend) ? to_f32<T>(base[e0 + k]) : -INFINITY;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int e0 = c0 + (j * kThreads + tid) * VN;
+            idx0[j] = e0;
+#pragma unroll
+            for (int k = 0; k < VN; ++k) x[j * VN + k] = (e0 + k < cend) ? to_f32<T>(base[e0 + k]) : -INFINITY;
+        }
+    }
+
+    // per-thread argmax in ascending index order: strict '>' keeps the lowest index
+    MaxIdx best = {-INFINITY, 0x7FFFFFFF};
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int k = 0; k < VN; ++k)
+            if (x[j * VN + k] > best.v) { best.v = x[j * VN + k]; best.i = idx0[j] + k; }
+    best = wave_best(best);
+
+    __shared__ float s_v[4];
+    __shared__ int32_t s_i[4];
+    __shared__ float s_s[4];
+    const int wave = tid >> 6, lane = tid & 63;
+    if (lane == 0) { s_v[wave] = best.v; s_i[wave] = best.i; }
+    __syncthreads();
+    MaxIdx blk = {s_v[0], s_i[0]};
+#pragma unroll
+    for (int w = 1; w < 4; ++w) blk = better(blk, MaxIdx{s_v[w], s_i[w]});
+
+    float sum = 0.f;
+    if (a.mode == S4C_STOCHASTIC) {
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) sum += fast_exp2((x[e] - blk.v) * a.inv_temp_log2);   // padding: exp2(-inf) = 0
+        sum = wave_sum(sum);
+        if (lane == 0) s_s[wave] = sum;
+        __syncthreads();
+        sum = (s_s[0] + s_s[1]) + (s_s[2] + s_s[3]);
+    }
+    if (tid == 0) {
+        const size_t o = (size_t)row * a.chunks + ch;
+        a.ws_max[o] = blk.v;
+        a.ws_arg[o] = blk.i;
+        a.ws_sum[o] = sum;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
+    const int b = blockIdx.x, i = threadIdx.x;
+    const int N = a.N;
+    __shared__ int32_t spar[kMaxNodes];
+    __shared__ int32_t s_ok[kMaxNodes];
+    __shared__ int32_t s_g[kMaxNodes];
+    __shared__ int32_t s_best;
+
+    // ---- tree validation: node 0 is the only root, parents precede children
+    int bad = 0;
+    if (i < N) {
+        const int p = a.parent[(size_t)b * N + i];
+        spar[i] = p;
+        bad = (i == 0) ? (p != -1) : (p < 0 || p >= i);
+    }
+    if (i == 0) s_best = 0;
+    bad = __syncthreads_or(bad);
+
+    // ---- combine the chunk statistics of row i
+    float m = -INFINITY, S = 0.f;
+    int32_t g = 0x7FFFFFFF;
+    if (i < N) {
+        const size_t o = ((size_t)b * N + i) * a.chunks;
+        for (int c = 0; c < a.chunks; ++c) {
+            const float v = a.ws_max[o + c];
+            if (v > m) { m = v; g = a.ws_arg[o + c]; }           // chunks ascend: strict '>' keeps lowest index
+        }
+        if (a.mode == S4C_STOCHASTIC)
+            for (int c = 0; c < a.chunks; ++c)
+                S += a.ws_sum[o + c] * fast_exp2((a.ws_max[o + c] - m) * a.inv_temp_log2);
+        s_g[i] = g;
+    }
+    __shared__ float s_m[kMaxNodes], s_S[kMaxNodes];
+    if (i < N) { s_m[i] = m; s_S[i] = S; }
+    __syncthreads();
+
+    int depth = 0;
+    if (!bad && i < N) {
+        // ---- local test of node i against its parent's row
+        int ok = 1;
+        if (i > 0) {
+            const int p = spar[i];
+            const int tok = a.tokens[(size_t)b * N + i];
+            if (a.mode == S4C_GREEDY) {
+                ok = (tok == s_g[p]);
+            } else if (tok < 0 || tok >= a.V) {
+                ok = 0;
+            } else {
+                const float lx = to_f32<T>(((const T*)a.logits)[((size_t)b * N + p) * a.V + tok]);
+                const float pt = fast_exp2((lx - s_m[p]) * a.inv_temp_log2) / s_S[p];
+                const float lhs = a.uniforms[(size_t)b * N + i] * a.p_draft[(size_t)b * N + i];
+                ok = (lhs < pt);
+            }
+        }
+        s_ok[i] = ok;
+    }
+    __syncthreads();
+    int accepted = 0;
+    if (!bad && i < N) {
+        accepted = 1;
+        for (int j = i; j > 0; j = spar[j]) { accepted &= s_ok[j]; ++depth; }
+        if (depth >= a.max_path) bad = 1;
+    }
+    bad = __syncthreads_or(bad);
+
+    int32_t* pth = a.path + (size_t)b * a.max_path;
+    int32_t* atk = a.accepted_tokens + (size_t)b * a.max_path;
+    for (int k = i; k < a.max_path; k += kMaxNodes) { pth[k] = (k == 0) ? 0 : -1; atk[k] = -1; }
+    if (bad) {
+        if (i == 0) {
+            a.accept_len[b] = 0;
+            a.bonus_token[b] = -1;
+            if (a.status) a.status[b] = S4C_SEQ_BAD_TREE;
+        }
+        return;
+    }
+    // deepest accepted node, lowest index among equals: maximise depth*256 + (255 - i)
+    if (accepted && i < N) atomicMax(&s_best, depth * 256 + (255 - i));
+    __syncthreads();
+    const int best = 255 - (s_best & 255);
+    if (i == best) {
+        const int L = depth;
+        int node = i;
+        for (int k = L; k >= 1; --k) {
+            pth[k] = node;
+            atk[k - 1] = a.tokens[(size_t)b * N + node];
+            node = spar[node];
+        }
+        a.accept_len[b] = L;
+        a.bonus_token[b] = (a.mode == S4C_GREEDY) ? s_g[i] : -1;
+        if (a.status) a.status[b] = 0;
+    }
+}
+
+}  // namespace
+
+int accept_chunk_elems() { return kChunk; }
+
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)(a.chunks * a.B * a.N)), block(kThreads);
+    if (a.dtype == S4C_F32) hipLaunchKernelGGL(row_stats_kernel<float>, grid, block, 0, st, a);
+    else hipLaunchKernelGGL(row_stats_kernel<bf16_t>, grid, block, 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (a.dtype == S4C_F32) hipLaunchKernelGGL(path_kernel<float>, dim3(a.B), dim3(kMaxNodes), 0, st, a);
+    else hipLaunchKernelGGL(path_kernel<bf16_t>, dim3(a.B), dim3(kMaxNodes), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace s4c

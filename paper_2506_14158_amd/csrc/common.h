@@ -1,0 +1,97 @@
+// Internal declarations shared by the HIP translation units of libs4c (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "s4c.h"
+
+namespace s4c {
+
+constexpr int kMaxNodes = 128;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef uint16_t bf16_t;   // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// round-to-nearest-even; inputs are finite
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return bf16_to_f32(x); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Arguments of the attention kernels.  Row r of the M = N*G query rows of one (sequence, KV
+// head) is node r / G, group head r % G.
+struct AttnArgs {
+    const void* q;
+    const void* k_tree;
+    const void* v_tree;
+    const void* k_cache;
+    const void* v_cache;
+    const int32_t* cache_len;
+    const int32_t* parent;
+    void* out;
+    int32_t* status;
+    float* ws_o;    // [B][Hkv][splits][M][D]  unnormalised partial outputs
+    float* ws_ml;   // [B][Hkv][splits][M][2]  (running max in log2 units, running sum)
+    int32_t B, Hq, Hkv, D, N, S_cap, G, M;
+    int32_t max_cache_len;
+    int32_t splits;   // KV splits; 1 => kernels write `out` directly
+    int32_t chunk;    // prefix keys per split (multiple of the key tile)
+    float scale_log2; // softmax scale * log2(e)
+};
+
+// launchers (defined in the kernel translation units); return hipGetLastError()
+hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st);
+bool mfma_path_supported(const s4c_attn_shape& s);
+int mfma_rows_per_block(const s4c_attn_shape& s);
+
+struct AcceptArgs {
+    const void* logits;
+    const int32_t* parent;
+    const int32_t* tokens;
+    const float* p_draft;
+    const float* uniforms;
+    int32_t* path;
+    int32_t* accept_len;
+    int32_t* accepted_tokens;
+    int32_t* bonus_token;
+    int32_t* status;
+    float* ws_max;     // [B*N][chunks]
+    int32_t* ws_arg;   // [B*N][chunks]
+    float* ws_sum;     // [B*N][chunks]
+    int32_t B, N, V, chunks, chunk_elems, max_path, mode, dtype;
+    float inv_temp_log2;   // log2(e) / T
+};
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
+int accept_chunk_elems();
+
+struct CompactArgs {
+    const void* k_tree;
+    const void* v_tree;
+    void* k_cache;
+    void* v_cache;
+    int32_t* cache_len;
+    const int32_t* path;
+    const int32_t* accept_len;
+    int32_t* dst_index;
+    int32_t* status;
+    int32_t B, Hkv, N, S_cap, max_path;
+    int32_t row_bytes;   // D * element size
+};
+hipError_t launch_compact(const CompactArgs& a, hipStream_t st);
+
+}  // namespace s4c

@@ -1,0 +1,190 @@
+// C ABI of libs4c: argument checks, launch planning, kernel launches.  See include/s4c.h.
+#include "common.h"
+
+#include <math.h>
+
+using namespace s4c;
+
+namespace {
+
+bool shape_ok(const s4c_attn_shape* s, s4c_status* why) {
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->D <= 0 || s->N <= 0 || s->S_cap < 0 ||
+        s->Hq % s->Hkv != 0) {
+        *why = S4C_ERR_SHAPE;
+        return false;
+    }
+    if (s->N > kMaxNodes || (s->D != 64 && s->D != 128) || (s->dtype != S4C_F32 && s->dtype != S4C_BF16) ||
+        s->B > 65535 || s->Hkv > 65535) {
+        *why = S4C_ERR_UNSUPPORTED;
+        return false;
+    }
+    return true;
+}
+
+struct AttnPlan {
+    bool mfma;
+    int splits;
+    int chunk;
+    size_t ws_o_bytes, ws_ml_bytes;
+};
+
+// Fixed function of (shape, max_cache_len): the same inputs always get the same split count
+// and therefore bit-identical results.
+AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
+    AttnPlan p;
+    p.mfma = mfma_path_supported(s);
+    const int M = s.N * (s.Hq / s.Hkv);
+    const int rows = p.mfma ? mfma_rows_per_block(s) : 32;
+    const long mtiles = (M + rows - 1) / rows;
+    const long units = (long)s.B * s.Hkv * mtiles;
+    const long target = 1024;                     // ~4 workgroups per CU on 256 CUs
+    long splits = (target + units - 1) / units;
+    const long max_splits = max_cache_len / 512 > 1 ? max_cache_len / 512 : 1;   // >= 512 keys per split
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    long chunk = (max_cache_len + splits - 1) / splits;
+    chunk = ((chunk + 127) / 128) * 128;
+    if (chunk < 128) chunk = 128;
+    splits = (max_cache_len + chunk - 1) / chunk;
+    if (splits < 1) splits = 1;
+    p.splits = (int)splits;
+    p.chunk = (int)chunk;
+    if (p.splits == 1) {
+        p.ws_o_bytes = p.ws_ml_bytes = 0;
+    } else {
+        const size_t prow = (size_t)s.B * s.Hkv * p.splits * M;
+        p.ws_o_bytes = prow * s.D * sizeof(float);
+        p.ws_ml_bytes = ((prow * 2 * sizeof(float) + 255) / 256) * 256;
+    }
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* s4c_strerror(s4c_status code) {
+    switch (code) {
+        case S4C_OK: return "ok";
+        case S4C_ERR_NULL: return "a required pointer is NULL";
+        case S4C_ERR_SHAPE: return "non-positive or inconsistent sizes";
+        case S4C_ERR_UNSUPPORTED: return "unsupported size, dtype or mode (N <= 128, D in {64,128})";
+        case S4C_ERR_WORKSPACE: return "workspace missing or too small";
+        case S4C_ERR_HIP: return "HIP kernel launch failed";
+    }
+    return "unknown status";
+}
+
+size_t s4c_tree_attn_workspace_size(const s4c_attn_shape* shape, int32_t max_cache_len) {
+    s4c_status why;
+    if (!shape || !shape_ok(shape, &why) || max_cache_len < 0) return 0;
+    const AttnPlan p = plan_attn(*shape, max_cache_len);
+    return p.ws_o_bytes + p.ws_ml_bytes;
+}
+
+int32_t s4c_tree_attn_num_splits(const s4c_attn_shape* shape, int32_t max_cache_len) {
+    s4c_status why;
+    if (!shape || !shape_ok(shape, &why) || max_cache_len < 0) return 0;
+    return plan_attn(*shape, max_cache_len).splits;
+}
+
+s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void* k_tree,
+                         const void* v_tree, const void* k_cache, const void* v_cache,
+                         const int32_t* cache_len, const int32_t* parent, int32_t max_cache_len,
+                         float scale, void* out, int32_t* status, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    if (!shape || !q || !k_tree || !v_tree || !cache_len || !parent || !out) return S4C_ERR_NULL;
+    s4c_status why;
+    if (!shape_ok(shape, &why)) return why;
+    if (max_cache_len < 0 || max_cache_len > shape->S_cap) return S4C_ERR_SHAPE;
+    if (max_cache_len > 0 && (!k_cache || !v_cache)) return S4C_ERR_NULL;
+    const AttnPlan p = plan_attn(*shape, max_cache_len);
+    const size_t need = p.ws_o_bytes + p.ws_ml_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255))) return S4C_ERR_WORKSPACE;
+
+    AttnArgs a;
+    a.q = q; a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.cache_len = cache_len; a.parent = parent; a.out = out; a.status = status;
+    a.ws_ml = (float*)workspace;
+    a.ws_o = (float*)((char*)workspace + p.ws_ml_bytes);
+    a.B = shape->B; a.Hq = shape->Hq; a.Hkv = shape->Hkv; a.D = shape->D; a.N = shape->N;
+    a.S_cap = shape->S_cap; a.G = shape->Hq / shape->Hkv; a.M = a.N * a.G;
+    a.max_cache_len = max_cache_len; a.splits = p.splits; a.chunk = p.chunk;
+    a.scale_log2 = (scale > 0.f ? scale : 1.0f / sqrtf((float)shape->D)) * kLog2e;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = p.mfma ? launch_tree_attn_mfma(a, st) : launch_tree_attn_generic(a, shape->dtype, st);
+    if (e != hipSuccess) return S4C_ERR_HIP;
+    if (p.splits > 1) {
+        e = launch_attn_merge(a, shape->dtype, st);
+        if (e != hipSuccess) return S4C_ERR_HIP;
+    }
+    return S4C_OK;
+}
+
+size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V) {
+    if (B <= 0 || N <= 0 || V <= 0) return 0;
+    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
+    const size_t per = (((size_t)B * N * chunks * 4 + 255) / 256) * 256;
+    return 3 * per;
+}
+
+s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
+                           float temperature, const void* logits, const int32_t* parent,
+                           const int32_t* tokens, const float* p_draft, const float* uniforms,
+                           int32_t max_path, int32_t* path, int32_t* accept_len,
+                           int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!logits || !parent || !tokens || !path || !accept_len || !accepted_tokens || !bonus_token)
+        return S4C_ERR_NULL;
+    if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0) return S4C_ERR_SHAPE;
+    if (N > kMaxNodes || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16) ||
+        (mode != S4C_GREEDY && mode != S4C_STOCHASTIC))
+        return S4C_ERR_UNSUPPORTED;
+    if (mode == S4C_STOCHASTIC) {
+        if (!p_draft || !uniforms) return S4C_ERR_NULL;
+        if (!(temperature > 0.f)) return S4C_ERR_SHAPE;
+    }
+    const size_t need = s4c_accept_path_workspace_size(B, N, V);
+    if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
+    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
+    if ((size_t)B * N * chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
+
+    AcceptArgs a;
+    a.logits = logits; a.parent = parent; a.tokens = tokens; a.p_draft = p_draft; a.uniforms = uniforms;
+    a.path = path; a.accept_len = accept_len; a.accepted_tokens = accepted_tokens;
+    a.bonus_token = bonus_token; a.status = status;
+    const size_t per = need / 3;
+    a.ws_max = (float*)workspace;
+    a.ws_arg = (int32_t*)((char*)workspace + per);
+    a.ws_sum = (float*)((char*)workspace + 2 * per);
+    a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)chunks; a.chunk_elems = accept_chunk_elems();
+    a.max_path = max_path; a.mode = mode; a.dtype = logits_dtype;
+    a.inv_temp_log2 = kLog2e / (mode == S4C_STOCHASTIC ? temperature : 1.0f);
+    return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
+s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const void* v_tree,
+                          void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                          const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
+                          int32_t* status, void* hip_stream) {
+    if (!shape || !k_tree || !v_tree || !k_cache || !v_cache || !cache_len || !path || !accept_len)
+        return S4C_ERR_NULL;
+    s4c_attn_shape s = *shape;
+    if (s.Hq <= 0) s.Hq = s.Hkv;          // Hq is not used by this call
+    if (s.Hkv > 0 && s.Hq % s.Hkv != 0) s.Hq = s.Hkv;
+    s4c_status why;
+    if (!shape_ok(&s, &why)) return why;
+    if (max_path <= 0 || s.S_cap <= 0) return S4C_ERR_SHAPE;
+
+    CompactArgs a;
+    a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.cache_len = cache_len; a.path = path; a.accept_len = accept_len; a.dst_index = dst_index;
+    a.status = status; a.B = s.B; a.Hkv = s.Hkv; a.N = s.N; a.S_cap = s.S_cap; a.max_path = max_path;
+    a.row_bytes = s.D * (s.dtype == S4C_F32 ? 4 : 2);
+    return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

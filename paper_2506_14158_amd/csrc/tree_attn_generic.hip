@@ -1,0 +1,255 @@
+// Tree-masked attention, scalar-FMA version (paper Sec. 3.2, Fig. 3).
+//
+// Used for fp32 data and for bf16 shapes the MFMA kernel does not take.  One workgroup owns
+// a tile of kBM query rows of one (sequence, KV head) and one KV split: it streams key/value
+// tiles of kBN rows through LDS, keeps a running max / sum per row (online softmax in log2
+// units) and an fp32 output accumulator in registers.  The prefix rows come from the cache;
+// the last split then walks the tree rows, where a score is kept only if the key node is the
+// query node or one of its ancestors (128-bit ancestor masks built from parent[] in LDS).
+// Also holds the merge kernel that combines the KV splits of either attention kernel.
+#include "common.h"
+
+namespace s4c {
+
+namespace {
+
+constexpr int kBM = 32;   // query rows per workgroup
+constexpr int kBN = 32;   // keys per tile
+constexpr int kThreads = 256;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void tree_attn_generic_kernel(AttnArgs a) {
+    __shared__ float Qs[kBM][D + 1];
+    __shared__ float Ks[kBN][D + 1];
+    __shared__ float Vs[kBN][D];
+    __shared__ float Ps[kBM][kBN + 1];
+    __shared__ int32_t spar[kMaxNodes];
+    __shared__ uint64_t anc_lo[kMaxNodes], anc_hi[kMaxNodes];
+
+    const int tid = threadIdx.x;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int mt = blockIdx.x / a.splits, sp = blockIdx.x % a.splits;
+    const int N = a.N, G = a.G, M = a.M;
+
+    const T* q = (const T*)a.q;
+    const T* kt = (const T*)a.k_tree;
+    const T* vt = (const T*)a.v_tree;
+    const T* kc = (const T*)a.k_cache + ((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap * D;
+    const T* vc = (const T*)a.v_cache + ((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap * D;
+
+    // ---- validate the sequence (every workgroup does; one of them reports)
+    int bad_tree = 0;
+    if (tid < N) {
+        const int p = a.parent[(size_t)b * N + tid];
+        spar[tid] = p;
+        bad_tree = (p < -1 || p >= tid);
+    }
+    bad_tree = __syncthreads_or(bad_tree);
+    const int P = a.cache_len[b];
+    const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    if (a.status && tid == 0 && blockIdx.x == 0 && kvh == 0)
+        a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
+    const bool bad = bad_tree || bad_len;
+
+    // ---- ancestor-or-self masks (only walked when parent[] is known to be valid)
+    if (tid < N && !bad) {
+        uint64_t lo = 0, hi = 0;
+        for (int j = tid; j >= 0; j = spar[j]) {
+            if (j < 64) lo |= 1ull << j; else hi |= 1ull << (j - 64);
+        }
+        anc_lo[tid] = lo;
+        anc_hi[tid] = hi;
+    }
+
+    // ---- stage the query tile
+    const int row0 = mt * kBM;
+    for (int e = tid; e < kBM * D; e += kThreads) {
+        const int lr = e / D, d = e % D;
+        const int r = row0 + lr;
+        float v = 0.f;
+        if (r < M) {
+            const int node = r / G, g = r % G;
+            v = to_f32<T>(q[(((size_t)b * N + node) * a.Hq + (kvh * G + g)) * D + d]);
+        }
+        Qs[lr][d] = v;
+    }
+    __syncthreads();
+
+    // thread -> (row, 4 key columns) for scores; (row, D/8 output columns) for the accumulator
+    const int lr = tid >> 3, sub = tid & 7;
+    const int r = row0 + lr;
+    const int node = (r < M) ? r / G : 0;
+    uint64_t my_lo = 0, my_hi = 0;
+    if (r < M && !bad) { my_lo = anc_lo[node]; my_hi = anc_hi[node]; }
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[D / 8];
+#pragma unroll
+    for (int j = 0; j < D / 8; ++j) acc[j] = 0.f;
+
+    int kb = sp * a.chunk, ke = min(P, (sp + 1) * a.chunk);
+    if (bad) { kb = 0; ke = 0; }
+    const int n_prefix_tiles = (ke > kb) ? (ke - kb + kBN - 1) / kBN : 0;
+    const int n_tree_tiles = (!bad && sp == a.splits - 1) ? (N + kBN - 1) / kBN : 0;
+
+    for (int t = 0; t < n_prefix_tiles + n_tree_tiles; ++t) {
+        const bool tree = t >= n_prefix_tiles;
+        const int k0 = tree ? (t - n_prefix_tiles) * kBN : kb + t * kBN;
+        const int kend = tree ? N : ke;
+        // ---- load K and V tile
+        for (int e = tid; e < kBN * D; e += kThreads) {
+            const int c = e / D, d = e % D;
+            const int kk = k0 + c;
+            float kvv = 0.f, vvv = 0.f;
+            if (kk < kend) {
+                if (tree) {
+                    const size_t off = (((size_t)b * N + kk) * a.Hkv + kvh) * D + d;
+                    kvv = to_f32<T>(kt[off]);
+                    vvv = to_f32<T>(vt[off]);
+                } else {
+                    const size_t off = (size_t)kk * D + d;
+                    kvv = to_f32<T>(kc[off]);
+                    vvv = to_f32<T>(vc[off]);
+                }
+            }
+            Ks[c][d] = kvv;
+            Vs[c][d] = vvv;
+        }
+        __syncthreads();
+
+        // ---- scores for (lr, sub + 8 j)
+        float s[4];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = sub + 8 * j;
+            const int kk = k0 + c;
+            float dot = 0.f;
+#pragma unroll 8
+            for (int d = 0; d < D; ++d) dot = fmaf(Qs[lr][d], Ks[c][d], dot);
+            bool vis = (kk < kend) && (r < M);
+            if (tree && vis) vis = (kk < 64) ? ((my_lo >> kk) & 1ull) : ((my_hi >> (kk - 64)) & 1ull);
+            s[j] = vis ? dot * a.scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, s[j]);
+        }
+        // row max across the 8 threads of the row
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 1));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 2));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 4));
+        const float m_new = fmaxf(m_run, tmax);
+        float alpha = 1.f, rsum = 0.f;
+        if (m_new > -INFINITY) {
+            alpha = fast_exp2(m_run - m_new);      // m_run = -inf -> 0
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p = fast_exp2(s[j] - m_new);   // masked -> 0
+                Ps[lr][sub + 8 * j] = p;
+                rsum += p;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Ps[lr][sub + 8 * j] = 0.f;
+        }
+        rsum += __shfl_xor(rsum, 1);
+        rsum += __shfl_xor(rsum, 2);
+        rsum += __shfl_xor(rsum, 4);
+        l_run = l_run * alpha + rsum;
+        m_run = m_new;
+        __syncthreads();
+
+        // ---- accumulate: acc[j] covers output column sub + 8 j
+#pragma unroll
+        for (int j = 0; j < D / 8; ++j) acc[j] *= alpha;
+        for (int c = 0; c < kBN; ++c) {
+            const float p = Ps[lr][c];
+#pragma unroll
+            for (int j = 0; j < D / 8; ++j) acc[j] = fmaf(p, Vs[c][sub + 8 * j], acc[j]);
+        }
+        __syncthreads();
+    }
+
+    if (r >= M) return;
+    const int g = r % G;
+    if (a.splits == 1) {
+        const float inv = (l_run > 0.f) ? 1.f / l_run : 0.f;
+        T* o = (T*)a.out + (((size_t)b * N + node) * a.Hq + (kvh * G + g)) * D;
+#pragma unroll
+        for (int j = 0; j < D / 8; ++j) o[sub + 8 * j] = from_f32<T>(acc[j] * inv);
+    } else {
+        const size_t prow = (((size_t)b * a.Hkv + kvh) * a.splits + sp) * M + r;
+        float* o = a.ws_o + prow * D;
+#pragma unroll
+        for (int j = 0; j < D / 8; ++j) o[sub + 8 * j] = acc[j];
+        if (sub == 0) {
+            a.ws_ml[prow * 2] = m_run;
+            a.ws_ml[prow * 2 + 1] = l_run;
+        }
+    }
+}
+
+// Combine the KV splits: one 64-lane wave per query row; fixed order => deterministic.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * 4 + wave;           // over B*Hkv*M
+    const size_t total = (size_t)a.B * a.Hkv * a.M;
+    if (row >= total) return;
+    const int r = (int)(row % a.M);
+    const size_t bh = row / a.M;
+    const int kvh = (int)(bh % a.Hkv), b = (int)(bh / a.Hkv);
+    float m = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.ws_ml[((bh * a.splits + s) * a.M + r) * 2]);
+    float l = 0.f;
+    float o[D / 64];
+#pragma unroll
+    for (int j = 0; j < D / 64; ++j) o[j] = 0.f;
+    if (m > -INFINITY) {
+        for (int s = 0; s < a.splits; ++s) {
+            const size_t prow = (bh * a.splits + s) * a.M + r;
+            const float ms = a.ws_ml[prow * 2], ls = a.ws_ml[prow * 2 + 1];
+            if (ls <= 0.f) continue;
+            const float w = fast_exp2(ms - m);
+            l += ls * w;
+#pragma unroll
+            for (int j = 0; j < D / 64; ++j) o[j] = fmaf(a.ws_o[prow * D + lane + 64 * j], w, o[j]);
+        }
+    }
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+    const int node = r / a.G, g = r % a.G;
+    T* dst = (T*)a.out + (((size_t)b * a.N + node) * a.Hq + (kvh * a.G + g)) * D;
+#pragma unroll
+    for (int j = 0; j < D / 64; ++j) dst[lane + 64 * j] = from_f32<T>(o[j] * inv);
+}
+
+}  // namespace
+
+hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st) {
+    const int mtiles = (a.M + kBM - 1) / kBM;
+    dim3 grid(mtiles * a.splits, a.Hkv, a.B), block(kThreads);
+    if (dtype == S4C_F32) {
+        if (a.D == 64) hipLaunchKernelGGL((tree_attn_generic_kernel<float, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((tree_attn_generic_kernel<float, 128>), grid, block, 0, st, a);
+    } else {
+        if (a.D == 64) hipLaunchKernelGGL((tree_attn_generic_kernel<bf16_t, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((tree_attn_generic_kernel<bf16_t, 128>), grid, block, 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st) {
+    const size_t rows = (size_t)a.B * a.Hkv * a.M;
+    dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (dtype == S4C_F32) {
+        if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<float, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attn_merge_kernel<float, 128>), grid, block, 0, st, a);
+    } else {
+        if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<bf16_t, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attn_merge_kernel<bf16_t, 128>), grid, block, 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+int generic_rows_per_block() { return kBM; }
+int generic_keys_per_tile() { return kBN; }
+
+}  // namespace s4c

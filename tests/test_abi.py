@@ -1,0 +1,97 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and
+rejects host-checkable mistakes before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2506_14158_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return B.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "s4c.h")).read()
+    declared = set(re.findall(r"\b(s4c_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_strerror(L):
+    assert B.s4c_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -77):
+        assert len(B.s4c_strerror(code)) > 0
+
+
+def shape(**kw):
+    d = dict(B=2, Hq=8, Hkv=2, D=128, N=64, S_cap=4096 + 64, dtype=B.S4C_BF16)
+    d.update(kw)
+    return B.AttnShape(**d)
+
+
+def test_workspace_queries(L):
+    s = shape()
+    assert B.s4c_tree_attn_num_splits(s, 4096) >= 1
+    n = B.s4c_tree_attn_workspace_size(s, 4096)
+    assert n % 256 == 0
+    assert B.s4c_tree_attn_workspace_size(shape(N=129), 4096) == 0
+    assert B.s4c_tree_attn_workspace_size(shape(Hq=7), 4096) == 0
+    assert B.s4c_accept_path_workspace_size(2, 64, 32000) > 0
+    assert B.s4c_accept_path_workspace_size(0, 64, 32000) == 0
+    # deterministic plan
+    assert B.s4c_tree_attn_num_splits(s, 4096) == B.s4c_tree_attn_num_splits(shape(), 4096)
+
+
+def test_tree_attn_host_errors(L):
+    s = shape()
+    one = C.c_void_p(256)          # never dereferenced: all of these fail before any launch
+    call = lambda sh, q=one, ws=None, wsb=0, mcl=4096: L.s4c_tree_attn(
+        C.byref(sh), q, one, one, one, one, one, one, mcl, 0.0, one, None, ws, wsb, None)
+    assert call(s, q=None) == -1
+    assert call(shape(N=200)) == -3
+    assert call(shape(D=96)) == -3
+    assert call(shape(dtype=7)) == -3
+    assert call(shape(Hq=7)) == -2
+    assert call(shape(B=0)) == -2
+    assert call(s, mcl=10 ** 6) == -2                      # max_cache_len beyond S_cap
+    if B.s4c_tree_attn_workspace_size(s, 4096) > 0:
+        assert call(s) == -4                               # workspace required but missing
+        assert call(s, ws=one, wsb=16) == -4
+
+
+def test_accept_and_compact_host_errors(L):
+    one = C.c_void_p(256)
+    acc = lambda Bn=2, N=8, V=100, dt=1, mode=0, T=1.0, logits=one, pd=one, ws=one, wsb=1 << 20, mp=4: \
+        L.s4c_accept_path(Bn, N, V, dt, mode, T, logits, one, one, pd, one, mp, one, one, one, one, None, ws, wsb, None)
+    assert acc(logits=None) == -1
+    assert acc(N=129) == -3
+    assert acc(mode=5) == -3
+    assert acc(dt=9) == -3
+    assert acc(V=0) == -2
+    assert acc(mp=0) == -2
+    assert acc(mode=1, pd=None) == -1
+    assert acc(mode=1, T=0.0) == -2
+    assert acc(ws=None) == -4
+    assert acc(wsb=8) == -4
+    s = shape()
+    cmp_ = lambda sh=s, kt=one, mp=4: L.s4c_kv_compact(C.byref(sh), kt, one, one, one, one, one, one, mp, None, None, None)
+    assert cmp_(kt=None) == -1
+    assert cmp_(sh=shape(D=100)) == -3
+    assert cmp_(mp=0) == -2
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libs4c.so")
+    with pytest.raises(FileNotFoundError):
+        B.lib()

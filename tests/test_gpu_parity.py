@@ -1,0 +1,266 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X: run with -m gpu).
+
+Attention: element by element at sizes the oracle finishes in seconds (several tiles, ragged
+tails, odd shapes), and on sampled outputs at the full config sizes in the launch shape the
+benchmark times.  Tolerances: bf16 I/O with fp32 accumulation max abs <= 1e-2 and row-relative
+<= 2e-2; fp32 <= 1e-5.  Acceptance and compaction: bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import s4c_oracle as O
+from paper_2506_14158_amd import binding as B, synth
+from paper_2506_14158_amd.verify import TreeVerifier
+from tests.util import accept_inputs_with_margin, attn_errors, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2)}
+C = synth.CONFIGS
+
+
+def verifier(cfg, d, max_cache_len=None):
+    return TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, cfg.S_cap, cfg.V, d["q"].dtype if "q" in d else
+                        (torch.float32 if cfg.dtype == "f32" else torch.bfloat16), cfg.levels,
+                        cfg.P if max_cache_len is None else max_cache_len)
+
+
+def check_attn_full(cfg, par=None, at=None, scale=0.0):
+    par = synth.make_parent(cfg) if par is None else par
+    at = synth.make_attn_inputs(cfg) if at is None else at
+    d = to_device(cfg, par, at)
+    tv = verifier(cfg, d)
+    tv.out.fill_(float("nan"))
+    tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"], scale)
+    torch.cuda.synchronize()
+    ref, st = O.tree_attn(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par, scale)
+    assert np.array_equal(tv.attn_status.cpu().numpy(), st)
+    assert torch.isfinite(tv.out.float()).all()
+    amax, rel = attn_errors(tv.out, ref)
+    assert amax <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1], (cfg.name, amax, rel)
+    return tv, d, amax, rel
+
+
+SMALL = [
+    C[1],                                                                        # Tiny, as specified
+    synth.scaled(C[1], name="tiny-noprefix", P=0, index=0),
+    synth.scaled(C[1], name="tiny-b3-ragged", B=3, P=77, ragged=True, index=0),
+    synth.scaled(C[1], name="f32-d128-gqa", Hq=6, Hkv=2, D=128, P=200, N=33, levels=6,
+                 widths=(3, 2, 2, 2, 2), complete_binary=False, index=0),
+    synth.scaled(C[2], name="7b-small", Hq=4, Hkv=4, P=333, index=0),            # ragged tail, N = 60
+    synth.scaled(C[2], name="7b-splits", Hq=2, Hkv=2, P=2500, index=0),          # forces KV splits
+    synth.scaled(C[3], name="13b-small", B=2, Hq=3, Hkv=3, P=1000, ragged=True, index=0),
+    synth.scaled(C[4], name="gqa-small", B=2, Hq=8, Hkv=2, P=640, index=0),
+    synth.scaled(C[5], name="70b-small", B=1, Hq=16, Hkv=2, P=520, index=0),     # N = 128, G = 8
+    synth.scaled(C[4], name="gqa-n1", B=2, Hq=8, Hkv=2, P=130, N=1, levels=1, index=0),
+    synth.scaled(C[4], name="gqa-d64", B=1, Hq=8, Hkv=4, D=64, P=257, N=37, levels=6, index=0),
+    synth.scaled(C[4], name="gqa-p0", B=2, Hq=4, Hkv=1, P=0, N=50, levels=6, index=0),
+    synth.scaled(C[4], name="gqa-p1", B=1, Hq=4, Hkv=1, P=1, N=17, levels=5, index=0),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_tree_attn_elementwise(cfg):
+    check_attn_full(cfg)
+
+
+def test_tree_attn_custom_scale_and_chain():
+    cfg = synth.scaled(C[2], name="chain", Hq=2, Hkv=2, P=100, N=40, levels=40, index=0)
+    par = np.arange(-1, cfg.N - 1, dtype=np.int32)[None]
+    check_attn_full(cfg, par=par, scale=0.05)
+
+
+def test_tree_attn_is_deterministic():
+    cfg = synth.scaled(C[3], name="det", B=2, Hq=4, Hkv=4, P=3000, index=0)
+    tv, d, _, _ = check_attn_full(cfg)
+    first = tv.out.clone()
+    for _ in range(3):
+        tv.out.zero_()
+        tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+        torch.cuda.synchronize()
+        assert torch.equal(tv.out.view(torch.int16), first.view(torch.int16))
+
+
+def test_tree_attn_flags_bad_sequences_and_zeroes_them():
+    cfg = synth.scaled(C[4], name="bad", B=3, Hq=4, Hkv=2, P=300, N=20, levels=5, index=0)
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    par[1, 7] = 9                       # parent after child
+    at.cache_len[2] = cfg.P + 5         # beyond max_cache_len
+    d = to_device(cfg, par, at)
+    tv = verifier(cfg, d)
+    tv.out.fill_(float("nan"))
+    tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+    torch.cuda.synchronize()
+    assert tv.attn_status.cpu().tolist() == [0, B.S4C_SEQ_BAD_TREE, B.S4C_SEQ_BAD_LEN]
+    assert (tv.out[1:] == 0).all()
+    at.cache_len[2] = cfg.P
+    ref, _ = O.tree_attn(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, synth.make_parent(cfg))
+    amax, rel = attn_errors(tv.out[0], ref[0])
+    assert amax <= 1e-2 and rel <= 2e-2
+
+
+def sample_triples(cfg, rng, n):
+    t = np.stack([rng.integers(0, cfg.B, n), rng.integers(0, cfg.N, n), rng.integers(0, cfg.Hq, n)], 1).astype(np.int32)
+    t[0] = (0, 0, 0)
+    t[1] = (cfg.B - 1, cfg.N - 1, cfg.Hq - 1)
+    return t
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_tree_attn_full_size_sampled(idx):
+    """Full config shape, benchmark launch configuration; the oracle evaluates sampled outputs."""
+    cfg = C[idx]
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg, threads=16)
+    d = to_device(cfg, par, at)
+    tv = verifier(cfg, d)
+    tv.out.fill_(float("nan"))
+    tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+    torch.cuda.synchronize()
+    out = tv.out.float().cpu().numpy()
+    assert np.isfinite(out).all()
+    n = 96 if idx < 5 else 48
+    bnh = sample_triples(cfg, np.random.default_rng(idx), n)
+    ref = O.tree_attn_sampled(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par, bnh)
+    got = np.stack([out[b, i, h] for b, i, h in bnh]).astype(np.float64)
+    amax = np.abs(got - ref).max()
+    rel = (np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)).max()
+    print("cfg%d sampled: max abs %.3e rel %.3e splits %d" % (idx, amax, rel, tv.num_splits))
+    assert amax <= 1e-2 and rel <= 2e-2
+    # property that holds at any size: the root row of every head only sees prefix + itself, so it
+    # must not change when every other tree node's K/V is scrambled
+    kt2 = d["k_tree"].clone()
+    kt2[:, 1:] = -kt2[:, 1:]
+    root_before = tv.out[:, 0].clone()
+    tv.tree_attn(d["q"], kt2, d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+    torch.cuda.synchronize()
+    assert torch.equal(tv.out[:, 0].view(torch.int16), root_before.view(torch.int16))
+
+
+# ------------------------------------------------------------------------------ acceptance
+def run_accept(cfg, par, ac):
+    d = to_device(cfg, par, None, ac)
+    tv = verifier(cfg, d)
+    mode = B.S4C_GREEDY if cfg.mode == "greedy" else B.S4C_STOCHASTIC
+    for t in (tv.path, tv.accept_len, tv.accepted_tokens, tv.bonus_token):
+        t.fill_(-7)
+    tv.accept_path(d["logits"], d["parent"], d["tokens"], mode, d["p_draft"], d["uniforms"], cfg.temperature)
+    torch.cuda.synchronize()
+    return tv
+
+
+def check_accept(cfg, par=None):
+    par = synth.make_parent(cfg) if par is None else par
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    tv = run_accept(cfg, par, ac)
+    assert np.array_equal(tv.accept_status.cpu().numpy(), r["status"])
+    assert np.array_equal(tv.path.cpu().numpy(), r["path"])
+    assert np.array_equal(tv.accept_len.cpu().numpy(), r["accept_len"])
+    assert np.array_equal(tv.accepted_tokens.cpu().numpy(), r["accepted_tokens"])
+    assert np.array_equal(tv.bonus_token.cpu().numpy(), r["bonus_token"])
+    return r
+
+
+ACCEPT_SMALL = [
+    C[1],
+    synth.scaled(C[1], name="tiny-v-odd", V=1003, B=3, index=0),                  # rows not 16-byte aligned
+    synth.scaled(C[2], name="7b-v-odd", V=8191 * 3 + 5, index=0),
+    synth.scaled(C[3], name="13b-small", B=2, V=9000, index=0),
+    synth.scaled(C[3], name="13b-temp", B=2, V=9000, temperature=0.7, index=0),
+    synth.scaled(C[5], name="70b-small", B=2, V=20000, index=0),
+    synth.scaled(C[1], name="f32-stochastic", mode="stochastic", B=4, V=5000, N=31, levels=5, index=0),
+]
+
+
+@pytest.mark.parametrize("cfg", ACCEPT_SMALL, ids=lambda c: c.name)
+def test_accept_path_small(cfg):
+    check_accept(cfg)
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_accept_path_full_size(idx):
+    r = check_accept(C[idx])
+    print("cfg%d accept_len" % idx, r["accept_len"].tolist())
+
+
+def test_accept_argmax_ties_and_hand_example():
+    """bf16 logits tie often; the lowest token id must win on the GPU exactly as in the oracle."""
+    rng = np.random.default_rng(3)
+    Bn, N, V = 2, 7, 40000
+    lg = synth.f32_to_bf16_bits(np.round(rng.standard_normal((Bn, N, V)).astype(np.float32) * 2))   # integers: massive ties
+    par = np.array([[-1, 0, 0, 1, 1, 2, 3]] * Bn, dtype=np.int32)
+    g, _, _ = O.row_stats(lg.reshape(-1, V))
+    g = g.reshape(Bn, N)
+    tokens = np.zeros((Bn, N), dtype=np.int32)
+    tokens[:, 1] = g[:, 0]; tokens[:, 2] = g[:, 0] + 1; tokens[:, 3] = g[:, 1] + 1; tokens[:, 4] = g[:, 1]
+    tokens[:, 5] = g[:, 2]; tokens[:, 6] = g[:, 3]
+    cfg = synth.scaled(C[2], name="ties", B=Bn, N=N, V=V, levels=4, index=0)
+    ac = synth.AcceptInputs(lg, tokens, np.zeros((Bn, N), np.float32), np.zeros((Bn, N), np.float32))
+    tv = run_accept(cfg, par, ac)
+    r = O.accept_path(lg, par, tokens, "greedy", cfg.levels)
+    assert tv.path.cpu().tolist() == [[0, 1, 4, -1]] * Bn == r["path"].tolist()
+    assert np.array_equal(tv.bonus_token.cpu().numpy(), g[:, 4])
+
+
+def test_accept_flags_bad_tree():
+    cfg = synth.scaled(C[1], name="bad", B=3, index=0)
+    par = synth.make_parent(cfg)
+    par[1, 3] = 5
+    par[2, 4] = -1                      # a second root
+    ac = synth.make_accept_inputs(cfg, synth.make_parent(cfg))
+    tv = run_accept(cfg, par, ac)
+    r = O.accept_path(ac.logits, par, ac.tokens, "greedy", cfg.levels)
+    assert tv.accept_status.cpu().tolist() == [0, 1, 1] == r["status"].tolist()
+    assert np.array_equal(tv.path.cpu().numpy(), r["path"])
+    assert np.array_equal(tv.accept_len.cpu().numpy(), r["accept_len"])
+    assert np.array_equal(tv.bonus_token.cpu().numpy(), r["bonus_token"])
+
+
+# ------------------------------------------------------------------------------ compaction + whole step
+@pytest.mark.parametrize("cfg", [C[1], synth.scaled(C[4], name="gqa-small", B=3, P=300, V=5000, ragged=True, index=0),
+                                 synth.scaled(C[5], name="70b-small", B=2, P=256, V=5000, index=0)],
+                         ids=lambda c: c.name)
+def test_whole_step_bit_exact_cache(cfg):
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    d = to_device(cfg, par, at, ac)
+    tv = verifier(cfg, d)
+    mode = B.S4C_GREEDY if cfg.mode == "greedy" else B.S4C_STOCHASTIC
+    tv.step(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"],
+            d["logits"], d["tokens"], mode, d["p_draft"], d["uniforms"], cfg.temperature)
+    torch.cuda.synchronize()
+    kc, vc, cl = at.k_cache.copy(), at.v_cache.copy(), at.cache_len.copy()
+    dst, st = O.kv_compact(at.k_tree, at.v_tree, kc, vc, cl, r["path"], r["accept_len"])
+    assert np.array_equal(tv.dst_index.cpu().numpy(), dst)
+    assert np.array_equal(tv.compact_status.cpu().numpy(), st)
+    assert np.array_equal(d["cache_len"].cpu().numpy(), cl)
+    bits = lambda t: t.cpu().contiguous().view(torch.uint8).numpy()
+    assert np.array_equal(bits(d["k_cache"]), kc.view(np.uint8))
+    assert np.array_equal(bits(d["v_cache"]), vc.view(np.uint8))
+    ref, _ = O.tree_attn(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par)
+    amax, rel = attn_errors(tv.out, ref)
+    assert amax <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1]
+
+
+def test_compact_rejects_overflow_and_bad_path():
+    cfg = synth.scaled(C[1], name="ovf", B=3, index=0)
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    d = to_device(cfg, par, at)
+    tv = verifier(cfg, d)
+    path = np.array([[0, 1, 3, -1], [0, 2, 99, -1], [0, 1, 4, 9]], dtype=np.int32)
+    alen = np.array([2, 2, 3], dtype=np.int32)
+    cl = np.array([cfg.P, cfg.P, cfg.S_cap - 2], dtype=np.int32)      # seq 2: 4 rows do not fit
+    tv.path.copy_(torch.from_numpy(path)); tv.accept_len.copy_(torch.from_numpy(alen))
+    d["cache_len"].copy_(torch.from_numpy(cl))
+    tv.kv_compact(d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"])
+    torch.cuda.synchronize()
+    kc, vc, cl2 = at.k_cache.copy(), at.v_cache.copy(), cl.copy()
+    dst, st = O.kv_compact(at.k_tree, at.v_tree, kc, vc, cl2, path, alen)
+    assert st.tolist() == [0, 2, 2] == tv.compact_status.cpu().tolist()
+    assert np.array_equal(tv.dst_index.cpu().numpy(), dst)
+    assert np.array_equal(d["cache_len"].cpu().numpy(), cl2)
+    assert np.array_equal(d["k_cache"].cpu().numpy(), kc) and np.array_equal(d["v_cache"].cpu().numpy(), vc)
