@@ -49,6 +49,7 @@ struct AttnArgs {
     int32_t max_cache_len;
     int32_t splits;   // KV splits; 1 => kernels write `out` directly
     int32_t chunk;    // prefix keys per split (multiple of the key tile)
+    int32_t mtiles;   // query-row tiles per (sequence, KV head); set by the launcher
     float scale_log2; // softmax scale * log2(e)
 };
 

@@ -37,9 +37,11 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
     const int rows = p.mfma ? mfma_rows_per_block(s) : 32;
     const long mtiles = (M + rows - 1) / rows;
     const long units = (long)s.B * s.Hkv * mtiles;
-    const long target = 1024;                     // ~4 workgroups per CU on 256 CUs
-    long splits = (target + units - 1) / units;
-    const long max_splits = max_cache_len / 512 > 1 ? max_cache_len / 512 : 1;   // >= 512 keys per split
+    // Workgroups that run at once: 256 CUs x (1 for the 4- and 8-wave MFMA kernels, 2 for the
+    // smaller ones, 4 for the scalar kernel).  Split the prefix only as far as that fills.
+    const long slots = 256 * (p.mfma ? (rows >= 128 ? 1 : 2) : 4);
+    long splits = slots / units;
+    const long max_splits = max_cache_len / 128 > 1 ? max_cache_len / 128 : 1;   // >= 128 keys per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     long chunk = (max_cache_len + splits - 1) / splits;

@@ -4,19 +4,24 @@
 // The N tree nodes times the G query heads that share one KV head form a dense tile of
 // M = N*G query rows, so both contractions run on v_mfma_f32_32x32x16_bf16.
 //   * One workgroup = WR waves; wave w owns 32 query rows.  All waves share the K/V tiles
-//     (64 keys) that the workgroup streams HBM -> registers -> LDS, double-buffered, with 16-byte
-//     coalesced loads; the next tile's loads are in flight while the current one is consumed.
+//     (64 keys) that the workgroup streams from HBM straight into LDS with
+//     global_load_lds_dwordx4 (no staging registers), through a ring of kStages tiles: the
+//     loads of tile t+kStages-1 are issued before tile t is consumed, so several tiles are in
+//     flight per CU while the matrix cores work.
 //   * Scores are computed transposed, S^T = K Q^T (A = K rows from LDS, B = Q^T kept in
 //     registers), so every lane owns one query row: the running max / sum and the rescaling of
 //     the output accumulator need no cross-lane traffic, and the exponentiated scores already
 //     sit in the B-operand layout of the second contraction O^T += V^T P^T.
 //   * V^T fragments come from the row-major V tile through the transposing LDS read
 //     (ds_read_b64_tr_b16), so V is never transposed in memory.
-//   * K rows are padded to 272 B and V rows to 320 B in LDS: conflict-free for the 16-byte row
-//     reads of K and for the 4-row x 64-byte transposing reads of V respectively.
+//   * A direct-to-LDS load writes 1 KB contiguous per wave, so rows cannot be padded; instead the
+//     16-byte chunks of a row are XOR-swizzled (K: chunk ^ (row & 15); V: chunk ^ ((row & 3) << 2)),
+//     applied on the global-address side of the load.  That makes the 16-byte row reads of K and
+//     the 4-row x 64-byte transposing reads of V bank-conflict free.
 //   * Prefix tiles need no mask.  The tree rows follow as extra tiles whose scores are kept only
 //     where the key node is the query node or one of its ancestors (128-bit masks built from
-//     parent[] in LDS).
+//     parent[] in LDS).  Rows past the end of a ragged tile are clamped to its last valid row
+//     (in-bounds, finite) and masked.
 //   * With KV splits > 1 the kernel writes unnormalised partials for the merge kernel.
 #include "common.h"
 
@@ -31,12 +36,26 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kD = 128;
-constexpr int kBN = 64;                 // keys per tile
-constexpr int kKStr = kD + 8;           // K row stride in LDS (elements): 272 B
-constexpr int kVStr = kD + 32;          // V row stride in LDS (elements): 320 B
-constexpr int kKBuf = kBN * kKStr;      // elements per K buffer
-constexpr int kVBuf = kBN * kVStr;
-constexpr int kLdsBytes = 2 * (kKBuf + kVBuf) * 2 + kMaxNodes * 16 + kMaxNodes * 4;
+constexpr int kBN = 64;                     // keys per tile
+constexpr int kRowB = kD * 2;               // bytes per K/V row
+constexpr int kTileB = kBN * kRowB;         // bytes per K (or V) tile: 16 KB
+constexpr int kStageB = 2 * kTileB;         // K then V
+constexpr int stages_for(int wr) { return wr == 1 ? 3 : 4; }   // vmcnt (6 bits) bounds the loads in flight
+constexpr int lds_bytes_for(int wr) { return stages_for(wr) * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
+
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+
+// One wave-wide direct-to-LDS load: lane i's 16 bytes at `g` land at LDS byte address
+// lds_base + 16 i (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
 
 template <int WR>
 __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
@@ -44,17 +63,26 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
     constexpr int BM = WR * 32;
     constexpr int CH = (kBN * kD / 8) / NT;      // 16-byte chunks per thread per K (or V) tile
     static_assert(CH >= 1, "tile smaller than the workgroup");
+    constexpr int kStages = stages_for(WR);
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* Ks = (bf16_t*)smem;                          // [2][kBN][kKStr]
-    bf16_t* Vs = Ks + 2 * kKBuf;                         // [2][kBN][kVStr]
-    uint32_t* anc = (uint32_t*)(Vs + 2 * kVBuf);         // [kMaxNodes][4]
-    int32_t* spar = (int32_t*)(anc + kMaxNodes * 4);     // [kMaxNodes]
+    uint32_t* anc = (uint32_t*)(smem + kStages * kStageB);   // [kMaxNodes][4]
+    int32_t* spar = (int32_t*)(anc + kMaxNodes * 4);         // [kMaxNodes]
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int mt = blockIdx.x / a.splits, sp = blockIdx.x % a.splits;
     const int N = a.N, G = a.G, M = a.M;
+
+    // Workgroups are handed to the 8 XCDs round-robin by linear id.  The `team` workgroups of
+    // one (sequence, KV head) -- its query-row tiles and KV splits -- take consecutive slots of
+    // ONE XCD, so the row tiles that stream the same K/V rows share that XCD's L2.
+    const int team = a.mtiles * a.splits;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int unit = (slot / team) * 8 + xcd;            // (sequence, KV head) index
+    if (unit >= a.B * a.Hkv) return;
+    const int member = slot % team;
+    const int mt = member / a.splits, sp = member % a.splits;
+    const int b = unit / a.Hkv, kvh = unit % a.Hkv;
 
     // ---- validate the sequence; build ancestor-or-self masks
     int bad_tree = 0;
@@ -66,7 +94,7 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
     bad_tree = __syncthreads_or(bad_tree);
     const int P = a.cache_len[b];
     const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
-    if (a.status && tid == 0 && blockIdx.x == 0 && kvh == 0)
+    if (a.status && tid == 0 && member == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
     const bool bad = bad_tree || bad_len;
     for (int i = tid; i < N && !bad; i += NT) {
@@ -113,40 +141,37 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
     const bf16_t* vt = (const bf16_t*)a.v_tree + ((size_t)b * N * a.Hkv + kvh) * kD;
     const size_t tree_stride = (size_t)a.Hkv * kD;
 
-    uint4 kreg[CH], vreg[CH];
-    auto load_tile = [&](int t) {
+    // ---- direct-to-LDS tile loads.  Instruction ii = wave + WR c of a tile covers rows
+    // 4 ii .. 4 ii + 3: lane -> (row 4 ii + lane/16, physical chunk lane%16), and fetches the logical
+    // chunk that the swizzle maps there.
+    auto issue_tile = [&](int t) {
         const bool tree = t >= n_pref;
         const int k0 = tree ? (t - n_pref) * kBN : kb + t * kBN;
-        const int kend = tree ? N : ke;
+        const int klast = (tree ? N : ke) - 1;
+        const bf16_t* kbase = tree ? kt : kc;
+        const bf16_t* vbase = tree ? vt : vc;
+        const size_t rstride = tree ? tree_stride : (size_t)kD;
+        const uint32_t sbase = lds0 + (uint32_t)(t % kStages) * kStageB;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
-            const int chunk = tid + NT * c;
-            const int row = chunk >> 4, col = (chunk & 15) * 8;
-            const int key = k0 + row;
-            uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-            if (key < kend) {
-                const size_t off = tree ? (size_t)key * tree_stride + col : (size_t)key * kD + col;
-                kv = *(const uint4*)((tree ? kt : kc) + off);
-                vv = *(const uint4*)((tree ? vt : vc) + off);
-            }
-            kreg[c] = kv;
-            vreg[c] = vv;
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const int chunk = tid + NT * c;
-            const int row = chunk >> 4, col = (chunk & 15) * 8;
-            *(uint4*)(Ks + buf * kKBuf + row * kKStr + col) = kreg[c];
-            *(uint4*)(Vs + buf * kVBuf + row * kVStr + col) = vreg[c];
+            const int ii = wave + WR * c;
+            const int row = 4 * ii + (lane >> 4), pc = lane & 15;
+            const size_t roff = (size_t)min(k0 + row, klast) * rstride;
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(sbase + ii * 1024);
+            dma16(kbase + roff + ((pc ^ (row & 15)) << 3), dst);
+            dma16(vbase + roff + ((pc ^ ((row & 3) << 2)) << 3), dst + kTileB);
         }
     };
 
-    // per-lane LDS offsets (elements)
-    const int k_lane_off = (lane & 31) * kKStr + g32 * 8;                          // + kblk*32*kKStr + 16 t
+    // per-lane LDS byte offsets inside a stage
     const int i16 = lane & 15, dhalf = (lane >> 4) & 1;
-    const int v_lane_off = (4 * g32 + (i16 >> 2)) * kVStr + 16 * dhalf + 4 * (i16 & 3);   // + key0*kVStr + 32 db
+    uint32_t k_off[8], v_off[4];
+#pragma unroll
+    for (int tt = 0; tt < 8; ++tt) k_off[tt] = (lane & 31) * kRowB + (((2 * tt + g32) ^ i16) << 4);
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        v_off[db] = kTileB + (4 * g32 + (i16 >> 2)) * kRowB +
+                    ((((db ^ (i16 >> 2)) << 2) + 2 * dhalf + ((i16 & 3) >> 1)) << 4) + 8 * (i16 & 1);
 
     f32x16 o[4];
 #pragma unroll
@@ -155,28 +180,42 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
         for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;      // l_run: this lane's half of the keys only
 
-    if (n_tiles > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
-    __syncthreads();
+    // The compiler does not see the direct-to-LDS loads; settle every load it does know about
+    // (the Q fragments) here, so that it places no vmcnt wait of its own inside the tile loop.
+    wait_vmcnt<0>();
+    for (int t = 0; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
 
     for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < n_tiles) load_tile(t + 1);
+        // tile t has landed once at most (kStages-2) younger tiles of this wave are outstanding
+        if (t + kStages - 2 < n_tiles) wait_vmcnt<2 * CH * (kStages - 2)>(); else wait_vmcnt<0>();
+        __syncthreads();          // every wave's part of tile t is in LDS; stage (t-1) % kStages is free
+        if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+        const unsigned char* stage = smem + (t % kStages) * kStageB;
 
-        // ---- S^T = K Q^T for the two 32-key blocks
+        // ---- S^T = K Q^T for the two 32-key blocks.  All K fragments of block 0 are requested
+        // first; block 1's fragments are requested while block 0's MFMAs run.
         f32x16 s[2];
+        {
+            bf16x8 kf[8];
 #pragma unroll
-        for (int kblk = 0; kblk < 2; ++kblk) {
+            for (int tt = 0; tt < 8; ++tt) kf[tt] = *(const bf16x8*)(stage + k_off[tt]);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s[kblk][j] = 0.f;
-            const bf16_t* kp = Ks + buf * kKBuf + kblk * 32 * kKStr + k_lane_off;
+            for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt) {
-                const bf16x8 ka = *(const bf16x8*)(kp + 16 * tt);
-                s[kblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[tt], s[kblk], 0, 0, 0);
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s[0], 0, 0, 0);
+                kf[tt] = *(const bf16x8*)(stage + 32 * kRowB + k_off[tt]);
             }
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt)
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s[1], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // 8 LDS reads
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);      // 8 MFMAs
         }
 
         // ---- masks: ragged tail of the prefix range / ancestor mask of the tree rows
@@ -228,27 +267,47 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
         }
         m_run = m_new;
 
-        // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T in four steps of 16 keys; the V^T fragments of step i+1 are
+        // requested before the MFMAs of step i.
+        {
+            bf16x8 pb[4];
 #pragma unroll
-        for (int kblk = 0; kblk < 2; ++kblk) {
+            for (int st = 0; st < 4; ++st)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                bf16x8 pb;
+                for (int e = 0; e < 8; ++e) pb[st][e] = (__bf16)s[st >> 1][8 * (st & 1) + e];
+            s16x4 vlo[2][4], vhi[2][4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)s[kblk][8 * u + e];
-                const bf16_t* vp = Vs + buf * kVBuf + (kblk * 32 + 16 * u) * kVStr + v_lane_off;
+            for (int db = 0; db < 4; ++db) {
+                vlo[0][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + v_off[db]));
+                vhi[0][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + 8 * kRowB + v_off[db]));
+            }
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                if (st < 3) {
+                    const unsigned char* vp = stage + (st + 1) * 16 * kRowB;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        vlo[(st + 1) & 1][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + v_off[db]));
+                        vhi[(st + 1) & 1][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kRowB + v_off[db]));
+                    }
+                }
 #pragma unroll
                 for (int db = 0; db < 4; ++db) {
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 32 * db));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kVStr + 32 * db));
-                    const s16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va), pb, o[db], 0, 0, 0);
+                    const s16x8 va = __builtin_shufflevector(vlo[st & 1][db], vhi[st & 1][db], 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va), pb[st], o[db], 0, 0, 0);
                 }
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
+#pragma unroll
+            for (int st = 0; st < 3; ++st) {
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                }
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
         }
-
-        if (t + 1 < n_tiles) store_tile(buf ^ 1);
-        __syncthreads();
     }
 
     // ---- write this lane's row: d = 32 db + 8 (j/4) + 4 g32 + (j%4)
@@ -289,13 +348,15 @@ hipError_t launch(const AttnArgs& a, hipStream_t st) {
     static bool attr_set = false;     // benign race: the attribute call is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_for(WR));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int mtiles = (a.M + WR * 32 - 1) / (WR * 32);
-    dim3 grid(mtiles * a.splits, a.Hkv, a.B), block(WR * 64);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR>), grid, block, kLdsBytes, st, a);
+    AttnArgs k = a;
+    k.mtiles = (a.M + WR * 32 - 1) / (WR * 32);
+    const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;          // padded to whole XCD rounds
+    dim3 grid((unsigned)(units8 * k.mtiles * a.splits)), block(WR * 64);
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR>), grid, block, lds_bytes_for(WR), st, k);
     return hipGetLastError();
 }
 
