@@ -5,24 +5,27 @@
 // M = N*G query rows, so both contractions run on v_mfma_f32_32x32x16_bf16.
 //   * One workgroup = WR waves; wave w owns 32 query rows.  All waves share the K/V tiles
 //     (64 keys) that the workgroup streams from HBM straight into LDS with
-//     global_load_lds_dwordx4 (no staging registers), through a ring of kStages tiles: the
-//     loads of tile t+kStages-1 are issued before tile t is consumed, so several tiles are in
-//     flight per CU while the matrix cores work.
+//     global_load_lds_dwordx4 (no staging registers), through a ring of NS tiles: the loads of
+//     tile t+NS-1 are issued before tile t is consumed, so several tiles are in flight per CU
+//     while the matrix cores work.
 //   * Scores are computed transposed, S^T = K Q^T (A = K rows from LDS, B = Q^T kept in
 //     registers), so every lane owns one query row: the running max / sum and the rescaling of
-//     the output accumulator need no cross-lane traffic, and the exponentiated scores already
-//     sit in the B-operand layout of the second contraction O^T += V^T P^T.
+//     the output accumulator need no cross-lane traffic (one v_permlane32_swap joins the two
+//     halves of a row), and the exponentiated scores already sit in the B-operand layout of the
+//     second contraction O^T += V^T P^T.
 //   * V^T fragments come from the row-major V tile through the transposing LDS read
 //     (ds_read_b64_tr_b16), so V is never transposed in memory.
 //   * A direct-to-LDS load writes 1 KB contiguous per wave, so rows cannot be padded; instead the
 //     16-byte chunks of a row are XOR-swizzled (K: chunk ^ (row & 15); V: chunk ^ ((row & 3) << 2)),
 //     applied on the global-address side of the load.  That makes the 16-byte row reads of K and
 //     the 4-row x 64-byte transposing reads of V bank-conflict free.
-//   * Prefix tiles need no mask.  The tree rows follow as extra tiles whose scores are kept only
-//     where the key node is the query node or one of its ancestors (128-bit masks built from
-//     parent[] in LDS).  Rows past the end of a ragged tile are clamped to its last valid row
-//     (in-bounds, finite) and masked.
+//   * Full prefix tiles run a mask-free body.  The ragged last prefix tile and the tree rows
+//     (extra tiles whose scores are kept only where the key node is the query node or one of its
+//     ancestors; 128-bit masks built from parent[] in LDS) run a masked copy of the body.  Rows
+//     past the end of a ragged tile are clamped to its last valid row (in bounds, finite).
 //   * With KV splits > 1 the kernel writes unnormalised partials for the merge kernel.
+#include <type_traits>
+
 #include "common.h"
 
 namespace s4c {
@@ -34,21 +37,34 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 
 constexpr int kD = 128;
 constexpr int kBN = 64;                     // keys per tile
 constexpr int kRowB = kD * 2;               // bytes per K/V row
 constexpr int kTileB = kBN * kRowB;         // bytes per K (or V) tile: 16 KB
 constexpr int kStageB = 2 * kTileB;         // K then V
-constexpr int stages_for(int wr) { return wr == 1 ? 3 : 4; }   // vmcnt (6 bits) bounds the loads in flight
-constexpr int lds_bytes_for(int wr) { return stages_for(wr) * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
+constexpr int lds_bytes_for(int ns) { return ns * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
 
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
+enum TileMode { kPlain = 0, kTail = 1, kTree = 2 };
 
-// One wave-wide direct-to-LDS load: lane i's 16 bytes at `g` land at LDS byte address
-// lds_base + 16 i (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.
+// One wave-wide direct-to-LDS load: lane i's 16 bytes land at LDS byte address lds_base + 16 i
+// (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+// Same with a wave-uniform 64-bit base and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+
+// Values that are wave-uniform by construction but that the compiler cannot prove uniform.
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const unsigned char*)(((uint64_t)hi << 32) | lo);
 }
 
 template <int N>
@@ -57,20 +73,28 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int WR>
-__global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
+// max(x[l], x[l ^ 32]) in every lane
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+template <int WR, int NS, int WPE>
+__global__ __launch_bounds__(WR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void tree_attn_mfma_kernel(AttnArgs a) {
     constexpr int NT = WR * 64;
     constexpr int BM = WR * 32;
-    constexpr int CH = (kBN * kD / 8) / NT;      // 16-byte chunks per thread per K (or V) tile
+    constexpr int CH = (kBN * kD / 8) / NT;      // direct-to-LDS loads per thread per K (or V) tile
     static_assert(CH >= 1, "tile smaller than the workgroup");
-    constexpr int kStages = stages_for(WR);
+    static_assert(NS >= 2 && 2 * CH * (NS - 2) < 64, "too many loads in flight for vmcnt");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint32_t* anc = (uint32_t*)(smem + kStages * kStageB);   // [kMaxNodes][4]
+    uint32_t* anc = (uint32_t*)(smem + NS * kStageB);        // [kMaxNodes][4]
     int32_t* spar = (int32_t*)(anc + kMaxNodes * 4);         // [kMaxNodes]
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int N = a.N, G = a.G, M = a.M;
 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  The `team` workgroups of
@@ -96,7 +120,8 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
     const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
     if (a.status && tid == 0 && member == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
-    const bool bad = bad_tree || bad_len;
+    // wave-uniform by construction; tell the compiler so that everything derived from it stays scalar
+    const bool bad = __builtin_amdgcn_readfirstlane((bad_tree || bad_len) ? 1 : 0) != 0;
     for (int i = tid; i < N && !bad; i += NT) {
         uint32_t m[4] = {0, 0, 0, 0};
         for (int j = i; j >= 0; j = spar[j]) m[j >> 5] |= 1u << (j & 31);
@@ -131,35 +156,54 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
     // ---- tiles of this workgroup: prefix range of the split, then (last split) the tree rows
     int kb = sp * a.chunk, ke = min(P, (sp + 1) * a.chunk);
     if (bad || ke < kb) { kb = 0; ke = 0; }
+    kb = uniform(kb);
+    ke = uniform(ke);
+    const int n_full = (ke - kb) / kBN;                          // mask-free prefix tiles
     const int n_pref = (ke - kb + kBN - 1) / kBN;
     const int n_tree = (!bad && sp == a.splits - 1) ? (N + kBN - 1) / kBN : 0;
     const int n_tiles = n_pref + n_tree;
 
-    const bf16_t* kc = (const bf16_t*)a.k_cache + ((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap * kD;
-    const bf16_t* vc = (const bf16_t*)a.v_cache + ((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap * kD;
-    const bf16_t* kt = (const bf16_t*)a.k_tree + ((size_t)b * N * a.Hkv + kvh) * kD;
-    const bf16_t* vt = (const bf16_t*)a.v_tree + ((size_t)b * N * a.Hkv + kvh) * kD;
-    const size_t tree_stride = (size_t)a.Hkv * kD;
+    const unsigned char* kc = (const unsigned char*)a.k_cache + (((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap + kb) * kRowB;
+    const unsigned char* vc = (const unsigned char*)a.v_cache + (((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap + kb) * kRowB;
+    const unsigned char* kt = (const unsigned char*)a.k_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
+    const unsigned char* vt = (const unsigned char*)a.v_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
+    const uint32_t tree_stride = (uint32_t)a.Hkv * kRowB;
 
-    // ---- direct-to-LDS tile loads.  Instruction ii = wave + WR c of a tile covers rows
-    // 4 ii .. 4 ii + 3: lane -> (row 4 ii + lane/16, physical chunk lane%16), and fetches the logical
-    // chunk that the swizzle maps there.
-    auto issue_tile = [&](int t) {
-        const bool tree = t >= n_pref;
-        const int k0 = tree ? (t - n_pref) * kBN : kb + t * kBN;
-        const int klast = (tree ? N : ke) - 1;
-        const bf16_t* kbase = tree ? kt : kc;
-        const bf16_t* vbase = tree ? vt : vc;
-        const size_t rstride = tree ? tree_stride : (size_t)kD;
-        const uint32_t sbase = lds0 + (uint32_t)(t % kStages) * kStageB;
+    // ---- direct-to-LDS tile loads.  Load c of a wave (instruction ii = wave + WR c of the tile)
+    // covers rows 4 ii .. 4 ii + 3: lane -> (row 4 ii + lane/16, physical chunk lane%16) and fetches
+    // the logical chunk that the swizzle maps there.  For full prefix tiles the per-lane byte
+    // offsets are loop invariants and the tile base advances in scalar registers.
+    uint32_t kvo_k[CH], kvo_v[CH];
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const int ii = wave + WR * c;
-            const int row = 4 * ii + (lane >> 4), pc = lane & 15;
-            const size_t roff = (size_t)min(k0 + row, klast) * rstride;
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(sbase + ii * 1024);
-            dma16(kbase + roff + ((pc ^ (row & 15)) << 3), dst);
-            dma16(vbase + roff + ((pc ^ ((row & 3) << 2)) << 3), dst + kTileB);
+    for (int c = 0; c < CH; ++c) {
+        const int row = 4 * (wave + WR * c) + (lane >> 4), pc = lane & 15;
+        kvo_k[c] = row * kRowB + ((pc ^ (row & 15)) << 4);
+        kvo_v[c] = row * kRowB + ((pc ^ ((row & 3) << 2)) << 4);
+    }
+    auto issue_tile = [&](int t) {
+        const uint32_t sbase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(t % NS) * kStageB + wave * 1024);
+        if (t < n_full) {
+            const unsigned char* kg = uniform(kc + (size_t)t * kTileB);
+            const unsigned char* vg = uniform(vc + (size_t)t * kTileB);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                dma16(kg, kvo_k[c], sbase + WR * c * 1024);
+                dma16(vg, kvo_v[c], sbase + WR * c * 1024 + kTileB);
+            }
+        } else {
+            const bool tree = t >= n_pref;
+            const int k0 = tree ? (t - n_pref) * kBN : t * kBN;             // relative to kb for the prefix
+            const int klast = (tree ? N : ke - kb) - 1;
+            const unsigned char* kg = uniform(tree ? kt : kc);
+            const unsigned char* vg = uniform(tree ? vt : vc);
+            const uint32_t rstride = tree ? tree_stride : (uint32_t)kRowB;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int row = 4 * (wave + WR * c) + (lane >> 4), pc = lane & 15;
+                const uint32_t roff = (uint32_t)min(k0 + row, klast) * rstride;
+                dma16(kg, roff + ((pc ^ (row & 15)) << 4), sbase + WR * c * 1024);
+                dma16(vg, roff + ((pc ^ ((row & 3) << 2)) << 4), sbase + WR * c * 1024 + kTileB);
+            }
         }
     };
 
@@ -180,31 +224,24 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
         for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;      // l_run: this lane's half of the keys only
 
-    // The compiler does not see the direct-to-LDS loads; settle every load it does know about
-    // (the Q fragments) here, so that it places no vmcnt wait of its own inside the tile loop.
-    wait_vmcnt<0>();
-    for (int t = 0; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
+    // ---- one tile: scores, (mask,) online softmax, accumulate
+    auto tile_body = [&](auto mode_tag, int t) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        const lds_u8* stage = (const lds_u8*)smem + (t % NS) * kStageB;     // LDS address space throughout
 
-    for (int t = 0; t < n_tiles; ++t) {
-        // tile t has landed once at most (kStages-2) younger tiles of this wave are outstanding
-        if (t + kStages - 2 < n_tiles) wait_vmcnt<2 * CH * (kStages - 2)>(); else wait_vmcnt<0>();
-        __syncthreads();          // every wave's part of tile t is in LDS; stage (t-1) % kStages is free
-        if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
-        const unsigned char* stage = smem + (t % kStages) * kStageB;
-
-        // ---- S^T = K Q^T for the two 32-key blocks.  All K fragments of block 0 are requested
-        // first; block 1's fragments are requested while block 0's MFMAs run.
+        // S^T = K Q^T for the two 32-key blocks.  All K fragments of block 0 are requested first;
+        // block 1's fragments are requested while block 0's MFMAs run.
         f32x16 s[2];
         {
             bf16x8 kf[8];
 #pragma unroll
-            for (int tt = 0; tt < 8; ++tt) kf[tt] = *(const bf16x8*)(stage + k_off[tt]);
+            for (int tt = 0; tt < 8; ++tt) kf[tt] = *(const lds_bf16x8*)(stage + k_off[tt]);
 #pragma unroll
             for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt) {
                 s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s[0], 0, 0, 0);
-                kf[tt] = *(const bf16x8*)(stage + 32 * kRowB + k_off[tt]);
+                kf[tt] = *(const lds_bf16x8*)(stage + 32 * kRowB + k_off[tt]);
             }
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt)
@@ -218,20 +255,19 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);      // 8 MFMAs
         }
 
-        // ---- masks: ragged tail of the prefix range / ancestor mask of the tree rows
-        const bool tree = t >= n_pref;
-        if (tree) {
-            const int tt0 = (t - n_pref) * 2;           // 32-key block index of kblk 0
+        // key of register j of block kblk, relative to the tile: 32 kblk + 8 (j/4) + 4 g32 + (j%4)
+        if constexpr (MODE == kTree) {
+            const int w0 = (t - n_pref) * 2;            // 32-node word of block 0
 #pragma unroll
             for (int kblk = 0; kblk < 2; ++kblk) {
-                const int w = tt0 + kblk;
+                const int w = w0 + kblk;
                 const uint32_t word = (w == 0 ? amask[0] : w == 1 ? amask[1] : w == 2 ? amask[2] : amask[3]) >> (4 * g32);
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
                     if (!((word >> ((j >> 2) * 8 + (j & 3))) & 1u)) s[kblk][j] = -INFINITY;
             }
-        } else if (t == n_pref - 1 && (ke - kb) % kBN != 0) {
-            const int nvalid = ke - (kb + t * kBN);
+        } else if constexpr (MODE == kTail) {
+            const int nvalid = (ke - kb) - t * kBN;
 #pragma unroll
             for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
@@ -239,15 +275,14 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
                     if (kblk * 32 + (j >> 2) * 8 + 4 * g32 + (j & 3) >= nvalid) s[kblk][j] = -INFINITY;
         }
 
-        // ---- online softmax for this lane's row (log2 units)
-        float mx = s[0][0];
+        // online softmax for this lane's row (log2 units)
+        float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int kblk = 0; kblk < 2; ++kblk)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kblk][j]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        for (int j = 1; j < 16; ++j) mx = fmaxf(mx, fmaxf(s[0][j], s[1][j]));
+        mx = max_across_halves(mx);
         const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        float m_safe = m_new;
+        if constexpr (MODE == kTree) m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // row with no visible key yet
         const float alpha = fast_exp2(m_run - m_safe);
         float psum = 0.f;
 #pragma unroll
@@ -267,47 +302,58 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
         }
         m_run = m_new;
 
-        // ---- O^T += V^T P^T in four steps of 16 keys; the V^T fragments of step i+1 are
-        // requested before the MFMAs of step i.
+        // O^T += V^T P^T in four steps of 16 keys; the V^T fragments of step i+1 are requested
+        // before the MFMAs of step i.
         {
             bf16x8 pb[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pb[st][e] = (__bf16)s[st >> 1][8 * (st & 1) + e];
-            s16x4 vlo[2][4], vhi[2][4];
+            auto vfrag = [&](const lds_u8* p) {     // 8 keys x 1 column of V^T: two transposing reads
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * kRowB));
+                return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            };
+            bf16x8 vf[2][4];
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                vlo[0][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + v_off[db]));
-                vhi[0][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + 8 * kRowB + v_off[db]));
-            }
+            for (int db = 0; db < 4; ++db) vf[0][db] = vfrag(stage + v_off[db]);
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
                 if (st < 3) {
-                    const unsigned char* vp = stage + (st + 1) * 16 * kRowB;
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        vlo[(st + 1) & 1][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + v_off[db]));
-                        vhi[(st + 1) & 1][db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kRowB + v_off[db]));
-                    }
+                    for (int db = 0; db < 4; ++db) vf[(st + 1) & 1][db] = vfrag(stage + (st + 1) * 16 * kRowB + v_off[db]);
                 }
 #pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const s16x8 va = __builtin_shufflevector(vlo[st & 1][db], vhi[st & 1][db], 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va), pb[st], o[db], 0, 0, 0);
-                }
+                for (int db = 0; db < 4; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st & 1][db], pb[st], o[db], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
-#pragma unroll
-            for (int st = 0; st < 3; ++st) {
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                }
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
         }
+    };
+
+    // The compiler does not see the direct-to-LDS loads; settle every load it does know about
+    // (the Q fragments) here, so that it places no vmcnt wait of its own inside the tile loop.
+    wait_vmcnt<0>();
+    for (int t = 0; t < NS - 1 && t < n_tiles; ++t) issue_tile(t);
+
+    auto sync_and_prefetch = [&](int t) {
+        // tile t has landed once at most NS-2 younger tiles of this wave are outstanding
+        if (t + NS - 2 < n_tiles) wait_vmcnt<2 * CH * (NS - 2)>(); else wait_vmcnt<0>();
+        __syncthreads();          // every wave's part of tile t is in LDS; stage (t-1) % NS is free
+        if (t + NS - 1 < n_tiles) issue_tile(t + NS - 1);
+    };
+    int t = 0;
+    for (; t < n_full; ++t) {
+        sync_and_prefetch(t);
+        tile_body(std::integral_constant<int, kPlain>{}, t);
+    }
+    for (; t < n_pref; ++t) {
+        sync_and_prefetch(t);
+        tile_body(std::integral_constant<int, kTail>{}, t);
+    }
+    for (; t < n_tiles; ++t) {
+        sync_and_prefetch(t);
+        tile_body(std::integral_constant<int, kTree>{}, t);
     }
 
     // ---- write this lane's row: d = 32 db + 8 (j/4) + 4 g32 + (j%4)
@@ -343,12 +389,13 @@ __global__ __launch_bounds__(WR * 64) void tree_attn_mfma_kernel(AttnArgs a) {
 
 int pick_wr(int M) { return M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8; }
 
-template <int WR>
+template <int WR, int NS, int WPE>
 hipError_t launch(const AttnArgs& a, hipStream_t st) {
+    constexpr int kLds = lds_bytes_for(NS);
     static bool attr_set = false;     // benign race: the attribute call is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_for(WR));
+        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR, NS, WPE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -356,7 +403,7 @@ hipError_t launch(const AttnArgs& a, hipStream_t st) {
     k.mtiles = (a.M + WR * 32 - 1) / (WR * 32);
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;          // padded to whole XCD rounds
     dim3 grid((unsigned)(units8 * k.mtiles * a.splits)), block(WR * 64);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR>), grid, block, lds_bytes_for(WR), st, k);
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR, NS, WPE>), grid, block, kLds, st, k);
     return hipGetLastError();
 }
 
@@ -368,10 +415,10 @@ int mfma_rows_per_block(const s4c_attn_shape& s) { return 32 * pick_wr(s.N * (s.
 
 hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st) {
     switch (pick_wr(a.M)) {
-        case 1: return launch<1>(a, st);
-        case 2: return launch<2>(a, st);
-        case 4: return launch<4>(a, st);
-        default: return launch<8>(a, st);
+        case 1: return launch<1, 3, 1>(a, st);
+        case 2: return launch<2, 4, 1>(a, st);
+        case 4: return launch<4, 4, 1>(a, st);
+        default: return launch<8, 4, 2>(a, st);
     }
 }
 
