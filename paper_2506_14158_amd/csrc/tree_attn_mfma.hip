@@ -229,23 +229,31 @@ void tree_attn_mfma_kernel(AttnArgs a) {
         constexpr int MODE = decltype(mode_tag)::value;
         const lds_u8* stage = (const lds_u8*)smem + (t % NS) * kStageB;     // LDS address space throughout
 
-        // S^T = K Q^T for the two 32-key blocks.  All K fragments of block 0 are requested first;
-        // block 1's fragments are requested while block 0's MFMAs run.
+        // S^T = K Q^T for the two 32-key blocks.  The two accumulator chains are interleaved (a
+        // dependent MFMA cannot start before its predecessor retires); the K fragments of the
+        // second half of the head dimension are requested while the first half is multiplied.
         f32x16 s[2];
         {
-            bf16x8 kf[8];
+            bf16x8 kf[2][4];
 #pragma unroll
-            for (int tt = 0; tt < 8; ++tt) kf[tt] = *(const lds_bf16x8*)(stage + k_off[tt]);
+            for (int tt = 0; tt < 4; ++tt) {
+                kf[0][tt] = *(const lds_bf16x8*)(stage + k_off[tt]);
+                kf[1][tt] = *(const lds_bf16x8*)(stage + 32 * kRowB + k_off[tt]);
+            }
 #pragma unroll
             for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
 #pragma unroll
-            for (int tt = 0; tt < 8; ++tt) {
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s[0], 0, 0, 0);
-                kf[tt] = *(const lds_bf16x8*)(stage + 32 * kRowB + k_off[tt]);
+            for (int tt = 0; tt < 4; ++tt) {
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][tt], qf[tt], s[0], 0, 0, 0);
+                kf[0][tt] = *(const lds_bf16x8*)(stage + k_off[tt + 4]);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][tt], qf[tt], s[1], 0, 0, 0);
+                kf[1][tt] = *(const lds_bf16x8*)(stage + 32 * kRowB + k_off[tt + 4]);
             }
 #pragma unroll
-            for (int tt = 0; tt < 8; ++tt)
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s[1], 0, 0, 0);
+            for (int tt = 0; tt < 4; ++tt) {
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][tt], qf[tt + 4], s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][tt], qf[tt + 4], s[1], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // 8 LDS reads
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt) {
@@ -278,7 +286,7 @@ void tree_attn_mfma_kernel(AttnArgs a) {
         // online softmax for this lane's row (log2 units)
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int j = 1; j < 16; ++j) mx = fmaxf(mx, fmaxf(s[0][j], s[1][j]));
+        for (int j = 1; j < 16; ++j) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[0][j]), s[1][j]);    // v_max3_f32
         mx = max_across_halves(mx);
         const float m_new = fmaxf(m_run, mx * a.scale_log2);
         float m_safe = m_new;
