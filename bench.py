@@ -140,7 +140,14 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": kv_bytes / t_attn / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = None      # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
+    try:
+        tr = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get("cfg%d" % cfg.index)
+        if tr:
+            roof["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
+            roof["traffic_over_algorithmic"] = roof["traffic"] / float(kv_bytes + 2 * cfg.B * cfg.N * cfg.Hq * cfg.D * es)
+    except (OSError, ValueError, KeyError):
+        pass
     roof["kernel"] = "s4c_tree_attn (%d KV split%s)" % (tv.num_splits, "" if tv.num_splits == 1 else "s + merge")
     roof["ms"] = t_attn * 1e3
 
