@@ -424,7 +424,7 @@ int mfma_rows_per_block(const s4c_attn_shape& s) { return 32 * pick_wr(s.N * (s.
 hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st) {
     switch (pick_wr(a.M)) {
         case 1: return launch<1, 3, 1>(a, st);
-        case 2: return launch<2, 4, 1>(a, st);
+        case 2: return launch<2, 2, 1>(a, st);       // 66 KB of LDS: two workgroups per CU
         case 4: return launch<4, 4, 1>(a, st);
         default: return launch<8, 4, 2>(a, st);
     }
