@@ -56,6 +56,7 @@ struct AttnArgs {
 // launchers (defined in the kernel translation units); return hipGetLastError()
 hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st);
+hipError_t launch_tree_attn_smallm(const AttnArgs& a, hipStream_t st);   // M <= 64, called by the above
 hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st);
 bool mfma_path_supported(const s4c_attn_shape& s);
 int mfma_rows_per_block(const s4c_attn_shape& s);

@@ -37,13 +37,21 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
     const int rows = p.mfma ? mfma_rows_per_block(s) : 32;
     const long mtiles = (M + rows - 1) / rows;
     const long units = (long)s.B * s.Hkv * mtiles;
-    // Workgroups that run at once: 256 CUs x (1 for the 4- and 8-wave MFMA kernels, 2 for the
-    // smaller ones, 4 for the scalar kernel).  Split the prefix only as far as that fills.
-    const long slots = 256 * (p.mfma ? (rows >= 128 ? 1 : 2) : 4);
-    long splits = slots / units;
-    const long max_splits = max_cache_len / 128 > 1 ? max_cache_len / 128 : 1;   // >= 128 keys per split
-    if (splits > max_splits) splits = max_splits;
-    if (splits < 1) splits = 1;
+    // Balance unit: the 256 CUs for the matrix-core kernels (HBM- or MFMA-bound: what counts is
+    // an equal share of work per CU), four workgroups per CU for the scalar kernel.  Split the prefix so that the launch fills
+    // whole rounds of the 256 CUs without paying for more partial results than that needs:
+    // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), at least 128 keys per split.
+    const long slots = 256 * (p.mfma ? 1 : 4);
+    long max_splits = max_cache_len / 128;
+    if (max_splits > 16) max_splits = 16;
+    if (max_splits < 1) max_splits = 1;
+    long splits = 1;
+    double best = 1e30;
+    for (long sp = 1; sp <= max_splits; ++sp) {
+        const long wgs = units * sp, rounds = (wgs + slots - 1) / slots;
+        const double cost = (double)(rounds * slots) / (double)wgs * (1.0 + 0.04 * (double)(sp - 1));
+        if (cost < best - 1e-9) { best = cost; splits = sp; }
+    }
     long chunk = (max_cache_len + splits - 1) / splits;
     chunk = ((chunk + 127) / 128) * 128;
     if (chunk < 128) chunk = 128;
@@ -116,13 +124,11 @@ s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void*
     a.scale_log2 = (scale > 0.f ? scale : 1.0f / sqrtf((float)shape->D)) * kLog2e;
 
     hipStream_t st = (hipStream_t)hip_stream;
+    // Splits are combined by a second kernel: the kernel boundary is what makes one workgroup's
+    // partial results visible to another across the chip's separate L2s at no extra cost.
     hipError_t e = p.mfma ? launch_tree_attn_mfma(a, st) : launch_tree_attn_generic(a, shape->dtype, st);
-    if (e != hipSuccess) return S4C_ERR_HIP;
-    if (p.splits > 1) {
-        e = launch_attn_merge(a, shape->dtype, st);
-        if (e != hipSuccess) return S4C_ERR_HIP;
-    }
-    return S4C_OK;
+    if (e == hipSuccess && p.splits > 1) e = launch_attn_merge(a, shape->dtype, st);
+    return e == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
 size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V) {

@@ -24,60 +24,19 @@
 //     ancestors; 128-bit masks built from parent[] in LDS) run a masked copy of the body.  Rows
 //     past the end of a ragged tile are clamped to its last valid row (in bounds, finite).
 //   * With KV splits > 1 the kernel writes unnormalised partials for the merge kernel.
-#include <type_traits>
-
-#include "common.h"
+#include "mfma_common.h"
 
 namespace s4c {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
-typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+using namespace mfma;
 
-constexpr int kD = 128;
 constexpr int kBN = 64;                     // keys per tile
-constexpr int kRowB = kD * 2;               // bytes per K/V row
 constexpr int kTileB = kBN * kRowB;         // bytes per K (or V) tile: 16 KB
 constexpr int kStageB = 2 * kTileB;         // K then V
 constexpr int lds_bytes_for(int ns) { return ns * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
 
-enum TileMode { kPlain = 0, kTail = 1, kTree = 2 };
-
-// One wave-wide direct-to-LDS load: lane i's 16 bytes land at LDS byte address lds_base + 16 i
-// (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.
-__device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
-}
-// Same with a wave-uniform 64-bit base and a 32-bit per-lane byte offset.
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
-}
-
-// Values that are wave-uniform by construction but that the compiler cannot prove uniform.
-__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
-__device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) {
-    const uint64_t v = (uint64_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return (const unsigned char*)(((uint64_t)hi << 32) | lo);
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
-// max(x[l], x[l ^ 32]) in every lane
-__device__ __forceinline__ float max_across_halves(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
 
 template <int WR, int NS, int WPE>
 __global__ __launch_bounds__(WR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
@@ -366,8 +325,8 @@ void tree_attn_mfma_kernel(AttnArgs a) {
 
     // ---- write this lane's row: d = 32 db + 8 (j/4) + 4 g32 + (j%4)
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (!rvalid) return;
     if (a.splits == 1) {
+        if (!rvalid) return;
         const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
         bf16_t* orow = (bf16_t*)a.out + (((size_t)b * N + node) * a.Hq + head) * kD + 4 * g32;
 #pragma unroll
@@ -380,22 +339,24 @@ void tree_attn_mfma_kernel(AttnArgs a) {
                 *(uint2*)(orow + 32 * db + 8 * jq) = pk;
             }
     } else {
-        const size_t prow = (((size_t)b * a.Hkv + kvh) * a.splits + sp) * M + rq;
-        float* orow = a.ws_o + prow * kD + 4 * g32;
+        if (rvalid) {
+            const size_t prow = (((size_t)b * a.Hkv + kvh) * a.splits + sp) * M + rq;
+            float* orow = a.ws_o + prow * kD + 4 * g32;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int jq = 0; jq < 4; ++jq)
-                *(float4*)(orow + 32 * db + 8 * jq) =
-                    make_float4(o[db][4 * jq], o[db][4 * jq + 1], o[db][4 * jq + 2], o[db][4 * jq + 3]);
-        if (g32 == 0) {
-            a.ws_ml[prow * 2] = m_run;
-            a.ws_ml[prow * 2 + 1] = l_tot;
+                for (int jq = 0; jq < 4; ++jq)
+                    *(float4*)(orow + 32 * db + 8 * jq) =
+                        make_float4(o[db][4 * jq], o[db][4 * jq + 1], o[db][4 * jq + 2], o[db][4 * jq + 3]);
+            if (g32 == 0) {
+                a.ws_ml[prow * 2] = m_run;
+                a.ws_ml[prow * 2 + 1] = l_tot;
+            }
         }
     }
 }
 
-int pick_wr(int M) { return M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8; }
+int pick_wr(int M) { return M <= 128 ? 4 : 8; }
 
 template <int WR, int NS, int WPE>
 hipError_t launch(const AttnArgs& a, hipStream_t st) {
@@ -419,15 +380,15 @@ hipError_t launch(const AttnArgs& a, hipStream_t st) {
 
 bool mfma_path_supported(const s4c_attn_shape& s) { return s.dtype == S4C_BF16 && s.D == kD; }
 
-int mfma_rows_per_block(const s4c_attn_shape& s) { return 32 * pick_wr(s.N * (s.Hq / s.Hkv)); }
+// Few rows: the key-parallel kernel (one 64-row workgroup); otherwise 32 rows per wave.
+int mfma_rows_per_block(const s4c_attn_shape& s) {
+    const int M = s.N * (s.Hq / s.Hkv);
+    return M <= 64 ? 64 : 32 * pick_wr(M);
+}
 
 hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st) {
-    switch (pick_wr(a.M)) {
-        case 1: return launch<1, 3, 1>(a, st);
-        case 2: return launch<2, 2, 1>(a, st);       // 66 KB of LDS: two workgroups per CU
-        case 4: return launch<4, 4, 1>(a, st);
-        default: return launch<8, 4, 2>(a, st);
-    }
+    if (a.M <= 64) return launch_tree_attn_smallm(a, st);
+    return pick_wr(a.M) == 4 ? launch<4, 4, 1>(a, st) : launch<8, 4, 2>(a, st);
 }
 
 }  // namespace s4c
