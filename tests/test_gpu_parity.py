@@ -57,6 +57,10 @@ SMALL = [
     synth.scaled(C[4], name="gqa-d64", B=1, Hq=8, Hkv=4, D=64, P=257, N=37, levels=6, index=0),
     synth.scaled(C[4], name="gqa-p0", B=2, Hq=4, Hkv=1, P=0, N=50, levels=6, index=0),
     synth.scaled(C[4], name="gqa-p1", B=1, Hq=4, Hkv=1, P=1, N=17, levels=5, index=0),
+    synth.scaled(C[2], name="7b-p0", Hq=2, Hkv=2, P=0, index=0),                 # few rows, tree only
+    synth.scaled(C[3], name="13b-p70", B=2, Hq=2, Hkv=2, P=70, N=33, levels=6, index=0),
+    synth.scaled(C[3], name="13b-p129", B=2, Hq=2, Hkv=1, P=129, N=32, levels=6, ragged=True, index=0),
+    synth.scaled(C[5], name="70b-mid", B=1, Hq=8, Hkv=1, P=300, N=16, levels=5, index=0),   # M = 128: 4-wave kernel
 ]
 
 
