@@ -187,38 +187,56 @@ __global__ __launch_bounds__(kThreads) void tree_attn_generic_kernel(AttnArgs a)
     }
 }
 
-// Combine the KV splits: one 64-lane wave per query row; fixed order => deterministic.
+// Combine the KV splits: 32 lanes per query row (D = 128: one float4 each; D = 64: float2),
+// all splits' loads issued before they are combined, fixed order => deterministic.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const size_t row = (size_t)blockIdx.x * 4 + wave;           // over B*Hkv*M
+    constexpr int kMaxS = 16;                                    // plan_attn never uses more splits
+    constexpr int VW = D / 32;                                   // floats per lane
+    const int sub = threadIdx.x & 31;
+    const size_t row = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);   // over B*Hkv*M
     const size_t total = (size_t)a.B * a.Hkv * a.M;
     if (row >= total) return;
     const int r = (int)(row % a.M);
     const size_t bh = row / a.M;
     const int kvh = (int)(bh % a.Hkv), b = (int)(bh / a.Hkv);
+    const int S = a.splits;
+    float ms[kMaxS], ls[kMaxS], v[kMaxS][VW];
+#pragma unroll
+    for (int s = 0; s < kMaxS; ++s) {
+        if (s < S) {
+            const size_t prow = (bh * S + s) * a.M + r;
+            ms[s] = a.ws_ml[prow * 2];
+            ls[s] = a.ws_ml[prow * 2 + 1];
+#pragma unroll
+            for (int j = 0; j < VW; ++j) v[s][j] = a.ws_o[prow * D + sub * VW + j];
+        } else {
+            ms[s] = -INFINITY;
+            ls[s] = 0.f;
+#pragma unroll
+            for (int j = 0; j < VW; ++j) v[s][j] = 0.f;
+        }
+    }
     float m = -INFINITY;
-    for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.ws_ml[((bh * a.splits + s) * a.M + r) * 2]);
-    float l = 0.f;
-    float o[D / 64];
 #pragma unroll
-    for (int j = 0; j < D / 64; ++j) o[j] = 0.f;
-    if (m > -INFINITY) {
-        for (int s = 0; s < a.splits; ++s) {
-            const size_t prow = (bh * a.splits + s) * a.M + r;
-            const float ms = a.ws_ml[prow * 2], ls = a.ws_ml[prow * 2 + 1];
-            if (ls <= 0.f) continue;
-            const float w = fast_exp2(ms - m);
-            l += ls * w;
+    for (int s = 0; s < kMaxS; ++s) m = fmaxf(m, ms[s]);
+    float l = 0.f, o[VW];
 #pragma unroll
-            for (int j = 0; j < D / 64; ++j) o[j] = fmaf(a.ws_o[prow * D + lane + 64 * j], w, o[j]);
+    for (int j = 0; j < VW; ++j) o[j] = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxS; ++s) {
+        if (ls[s] > 0.f) {
+            const float w = fast_exp2(ms[s] - m);
+            l += ls[s] * w;
+#pragma unroll
+            for (int j = 0; j < VW; ++j) o[j] = fmaf(v[s][j], w, o[j]);
         }
     }
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     const int node = r / a.G, g = r % a.G;
-    T* dst = (T*)a.out + (((size_t)b * a.N + node) * a.Hq + (kvh * a.G + g)) * D;
+    T* dst = (T*)a.out + (((size_t)b * a.N + node) * a.Hq + (kvh * a.G + g)) * D + sub * VW;
 #pragma unroll
-    for (int j = 0; j < D / 64; ++j) dst[lane + 64 * j] = from_f32<T>(o[j] * inv);
+    for (int j = 0; j < VW; ++j) dst[j] = from_f32<T>(o[j] * inv);
 }
 
 }  // namespace
@@ -238,7 +256,7 @@ hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st
 
 hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st) {
     const size_t rows = (size_t)a.B * a.Hkv * a.M;
-    dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    dim3 grid((unsigned)((rows + 7) / 8)), block(256);
     if (dtype == S4C_F32) {
         if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<float, 64>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((attn_merge_kernel<float, 128>), grid, block, 0, st, a);
