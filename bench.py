@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="1..5 (BASELINE configs); 5 is the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a captured HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 3 plain 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -165,6 +167,22 @@ def main():
         "accept_path_GBps": logits_bytes / t_acc / 1e9,
         "paper_context": "paper reports 2.26x-2.60x end-to-end vs autoregressive decoding (A100-40GB / 4xRTX4090, fp16, batch 1)",
     }
+    if args.graph:
+        # launch-bound configs: one graph launch instead of six kernel launches per step
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        rec["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, par, at, ac)
     print(json.dumps(rec))

@@ -268,3 +268,41 @@ def test_compact_rejects_overflow_and_bad_path():
     assert np.array_equal(tv.dst_index.cpu().numpy(), dst)
     assert np.array_equal(d["cache_len"].cpu().numpy(), cl2)
     assert np.array_equal(d["k_cache"].cpu().numpy(), kc) and np.array_equal(d["v_cache"].cpu().numpy(), vc)
+
+
+def test_step_replays_from_a_hip_graph():
+    """The three calls allocate nothing, never synchronise and use no memset nodes, so a step can be
+    captured once and replayed; every replay must reproduce the eager result."""
+    cfg = synth.scaled(C[4], name="graph", B=2, Hq=8, Hkv=2, P=1500, V=9000, index=0)     # KV splits + merge
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    d = to_device(cfg, par, at, ac)
+    tv = verifier(cfg, d)
+    mode = B.S4C_GREEDY
+    cl0 = d["cache_len"].clone()
+    kc0, vc0 = d["k_cache"].clone(), d["v_cache"].clone()
+
+    def step():
+        tv.step(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"],
+                d["logits"], d["tokens"], mode)
+    step()                                  # eager reference
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (tv.out, tv.path, tv.accept_len, tv.bonus_token, d["cache_len"], d["k_cache"], d["v_cache"])]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    d["cache_len"].copy_(cl0); d["k_cache"].copy_(kc0); d["v_cache"].copy_(vc0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    for rep in range(3):
+        d["cache_len"].copy_(cl0); d["k_cache"].copy_(kc0); d["v_cache"].copy_(vc0)       # eager work between replays
+        tv.out.zero_(); tv.path.fill_(-9); tv.accept_len.fill_(-9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (tv.out, tv.path, tv.accept_len, tv.bonus_token, d["cache_len"], d["k_cache"], d["v_cache"])
+        for a_, b_ in zip(got, ref):
+            assert torch.equal(a_.view(torch.uint8) if a_.dtype == torch.bfloat16 else a_,
+                               b_.view(torch.uint8) if b_.dtype == torch.bfloat16 else b_), rep
