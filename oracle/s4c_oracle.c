@@ -247,6 +247,126 @@ int oracle_accept_path(int32_t B, int32_t N, int32_t V, int32_t dtype, int32_t m
     return 0;
 }
 
+/* ------------------------------------------------------------------ sequential rule + correction token */
+
+/* target distribution of row `off` : r[v] = softmax(logits/T)[v] */
+static void target_dist(const void* logits, int32_t dtype, size_t off, int32_t V, double T, double* r) {
+    double m = load_elem(logits, dtype, off);
+    for (int32_t v = 1; v < V; ++v) {
+        const double x = load_elem(logits, dtype, off + v);
+        if (x > m) m = x;
+    }
+    double sum = 0.0;
+    for (int32_t v = 0; v < V; ++v) {
+        r[v] = exp((load_elem(logits, dtype, off + v) - m) / T);
+        sum += r[v];
+    }
+    for (int32_t v = 0; v < V; ++v) r[v] /= sum;
+}
+
+int oracle_accept_resample(int32_t B, int32_t N, int32_t V, int32_t dtype, double temperature,
+                           const void* logits, const float* draft_probs, const int32_t* parent,
+                           const int32_t* tokens, const float* uniforms, const float* u_resample,
+                           int32_t max_path, int32_t* path, int32_t* accept_len,
+                           int32_t* accepted_tokens, int32_t* bonus_token, double* margin_accept,
+                           double* margin_sample, int32_t* status) {
+    if (N < 1 || max_path < 1 || V < 1 || temperature <= 0.0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t* par = parent + (size_t)b * N;
+        const int32_t* tok = tokens + (size_t)b * N;
+        int32_t* pth = path + (size_t)b * max_path;
+        int32_t* atk = accepted_tokens + (size_t)b * max_path;
+        for (int32_t k = 0; k < max_path; ++k) { pth[k] = -1; atk[k] = -1; }
+        pth[0] = 0;
+        if (margin_accept) margin_accept[b] = INFINITY;
+        if (margin_sample) margin_sample[b] = INFINITY;
+
+        int bad = (par[0] != -1);
+        for (int32_t i = 1; i < N && !bad; ++i)
+            if (par[i] < 0 || par[i] >= i) bad = 1;
+        if (!bad) {
+            int32_t* depth = (int32_t*)malloc(sizeof(int32_t) * N);
+            depth[0] = 0;
+            for (int32_t i = 1; i < N; ++i) {
+                depth[i] = depth[par[i]] + 1;
+                if (depth[i] >= max_path) bad = 1;
+            }
+            free(depth);
+        }
+        if (bad) {
+            if (status) status[b] = ORACLE_BAD_TREE;
+            accept_len[b] = 0;
+            bonus_token[b] = -1;
+            continue;
+        }
+        if (status) status[b] = 0;
+
+        double* r = (double*)malloc(sizeof(double) * (size_t)V);   /* the distribution the next token must follow */
+        int32_t cur = 0, L = 0;
+        for (;;) {
+            target_dist(logits, dtype, ((size_t)b * N + cur) * V, V, temperature, r);
+            const float* q = draft_probs + ((size_t)b * N + cur) * V;   /* draft distribution at cur */
+            int32_t next = -1;
+            for (int32_t c = cur + 1; c < N && next < 0; ++c) {
+                if (par[c] != cur) continue;
+                const int32_t x = tok[c];
+                if (x < 0 || x >= V) continue;                 /* not a token: rejected, r unchanged */
+                const double lhs = (double)uniforms[(size_t)b * N + c] * (double)q[x];
+                const int ok = (lhs < r[x]);                   /* u < r(x)/q(x), strict */
+                if (margin_accept) {
+                    const double den = lhs > r[x] ? lhs : r[x];
+                    const double mg = den > 0.0 ? fabs(lhs - r[x]) / den : 0.0;
+                    if (mg < margin_accept[b]) margin_accept[b] = mg;
+                }
+                if (ok) {
+                    next = c;
+                } else {
+                    /* rejected: r <- norm(max(0, r - q))  (Sec. 2, speculative-sampling paragraph) */
+                    double Z = 0.0;
+                    for (int32_t v = 0; v < V; ++v) {
+                        const double d = r[v] - (double)q[v];
+                        Z += d > 0.0 ? d : 0.0;
+                    }
+                    if (Z > 0.0)
+                        for (int32_t v = 0; v < V; ++v) {
+                            const double d = r[v] - (double)q[v];
+                            r[v] = d > 0.0 ? d / Z : 0.0;
+                        }
+                }
+            }
+            if (next < 0) break;
+            pth[++L] = next;
+            atk[L - 1] = tok[next];
+            cur = next;
+        }
+        /* correction / bonus token: inverse CDF of r in token-id order */
+        double total = 0.0;
+        for (int32_t v = 0; v < V; ++v) total += r[v];
+        const double t = (double)u_resample[b] * total;
+        double run = 0.0;
+        int32_t pick = -1, last_pos = -1;
+        for (int32_t v = 0; v < V; ++v) {
+            const double prev = run;
+            run += r[v];
+            if (r[v] > 0.0) last_pos = v;
+            if (run > t) {
+                pick = v;
+                if (margin_sample) {
+                    const double lo = t - prev, hi = run - t;
+                    margin_sample[b] = (lo < hi ? lo : hi) / total;
+                }
+                break;
+            }
+        }
+        if (pick < 0) { pick = last_pos; if (margin_sample) margin_sample[b] = 0.0; }
+        accept_len[b] = L;
+        bonus_token[b] = pick;
+        free(r);
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ compaction */
 
 int oracle_kv_compact(const oracle_shape* s, const void* k_tree, const void* v_tree,

@@ -18,7 +18,9 @@
  * trees, chain tree == ordinary causal attention (library routine), closed forms (equal
  * keys -> mean of visible values, V == 1 -> output 1, empty prefix root -> V_root),
  * hand-worked acceptance examples, chain == sequential speculative-sampling rule,
- * compaction == appending accepted tokens one at a time.  Nothing here is unpinned.
+ * compaction == appending accepted tokens one at a time; sequential rule with correction:
+ * Monte-Carlo check that the emitted tokens follow the target distribution, hand-worked
+ * residuals, deterministic-draft and q == p closed forms.  Nothing here is unpinned.
  */
 #ifndef S4C_ORACLE_H
 #define S4C_ORACLE_H
@@ -67,6 +69,29 @@ int oracle_accept_path(int32_t B, int32_t N, int32_t V, int32_t dtype, int32_t m
                        int32_t max_path, int32_t* path, int32_t* accept_len,
                        int32_t* accepted_tokens, int32_t* bonus_token, double* margin,
                        int32_t* status);
+
+/* Sibling-sequential acceptance with the correction token (Sec. 2, speculative-sampling
+ * paragraph: a rejected token is redrawn from norm(max(0, p - q)); Sec. 3.2, second equation:
+ * the correction step at a fork of the tree, which refers to the multi-candidate scheme where
+ * the residual is carried from one rejected sibling to the next).
+ *   Walk from the root.  At node cur let r = softmax(logits[cur]/T) and q = draft_probs[cur]
+ *   (float [B][N][V]: the distribution the children of cur were proposed from).  The children of
+ *   cur are tried in increasing node index: child c with token x is accepted iff
+ *   uniforms[c] * q[x] < r[x] (strict); then cur = c and the walk continues with a fresh r.
+ *   Otherwise r <- norm(max(0, r - q)) (left unchanged if that has no mass, or if x is not a
+ *   token id) and the next sibling is tried.  When no child is accepted (or cur is a leaf) the
+ *   walk stops and bonus_token = the inverse CDF of r at u_resample[b]: the lowest v with
+ *   sum_{w<=v} r[w] > u_resample[b] * sum_w r[w].
+ *   path / accept_len / accepted_tokens / status as in oracle_accept_path.
+ *   margin_accept [B] (nullable): min over tests of |u q(x) - r(x)| / max(u q(x), r(x));
+ *   margin_sample [B] (nullable): distance of u * total to the nearer edge of the chosen
+ *                                 token's CDF interval, divided by total. */
+int oracle_accept_resample(int32_t B, int32_t N, int32_t V, int32_t dtype, double temperature,
+                           const void* logits, const float* draft_probs, const int32_t* parent,
+                           const int32_t* tokens, const float* uniforms, const float* u_resample,
+                           int32_t max_path, int32_t* path, int32_t* accept_len,
+                           int32_t* accepted_tokens, int32_t* bonus_token, double* margin_accept,
+                           double* margin_sample, int32_t* status);
 
 /* Row statistics used above, exposed for pins: lowest-index argmax, max, and
  * sum_v exp((l_v - max)/T) in double. */

@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -132,6 +132,33 @@ def accept_path(logits, parent, tokens, mode, max_path, p_draft=None, uniforms=N
                                 C.c_int32(max_path), _p(path), _p(alen), _p(atok), _p(bonus), _p(margin), _p(status))
     assert rc == 0, rc
     return dict(path=path, accept_len=alen, accepted_tokens=atok, bonus_token=bonus, margin=margin, status=status)
+
+
+def accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resample, max_path, temperature=1.0):
+    """Sibling-sequential rule with the correction token
+    -> dict(path, accept_len, accepted_tokens, bonus_token, margin_accept, margin_sample, status)"""
+    lib = _load()
+    B, N, V = logits.shape
+    parent, tokens = _i32(parent), _i32(tokens)
+    draft_probs = np.ascontiguousarray(draft_probs, dtype=np.float32)
+    assert draft_probs.shape == (B, N, V)
+    uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+    u_resample = np.ascontiguousarray(u_resample, dtype=np.float32)
+    assert uniforms.shape == (B, N) and u_resample.shape == (B,)
+    path = np.empty((B, max_path), dtype=np.int32)
+    atok = np.empty((B, max_path), dtype=np.int32)
+    alen = np.empty(B, dtype=np.int32)
+    bonus = np.empty(B, dtype=np.int32)
+    ma = np.empty(B, dtype=np.float64)
+    ms = np.empty(B, dtype=np.float64)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_accept_resample(C.c_int32(B), C.c_int32(N), C.c_int32(V), C.c_int32(_dt(logits)),
+                                    C.c_double(temperature), _p(logits), _p(draft_probs), _p(parent), _p(tokens),
+                                    _p(uniforms), _p(u_resample), C.c_int32(max_path), _p(path), _p(alen), _p(atok),
+                                    _p(bonus), _p(ma), _p(ms), _p(status))
+    assert rc == 0, rc
+    return dict(path=path, accept_len=alen, accepted_tokens=atok, bonus_token=bonus, margin_accept=ma,
+                margin_sample=ms, status=status)
 
 
 def kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len):
