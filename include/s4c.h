@@ -114,6 +114,32 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
                            int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Sibling-sequential acceptance with the correction token (Sec. 2, speculative-sampling
+ * paragraph: accept with probability min(1, p/q), redraw a rejected token from
+ * norm(max(0, p - q)); Sec. 3.2, second equation: the correction at a fork of the tree, where
+ * the corrected distribution is carried from one rejected sibling to the next).
+ *   logits      [B][N][V] (logits_dtype), row i = target distribution after node i
+ *   draft_probs [B][N][V] fp32, row i = the distribution the children of node i were proposed
+ *               from (rows of leaves are not read)
+ *   parent, tokens [B][N] as in s4c_accept_path; uniforms [B][N] fp32 in [0,1), entry 0 unused;
+ *   u_resample  [B] fp32 in [0,1)
+ *   The walk starts at the root.  At node cur, r = softmax(logits[cur]/T), q = draft_probs[cur].
+ *   The children of cur are tried in increasing node index: child c with token x is accepted iff
+ *   uniforms[c] * q[x] < r[x] (strict); the walk then moves to c with a fresh r.  After a
+ *   rejection r <- norm(max(0, r - q)) (unchanged if that has no mass; a child whose token is
+ *   not in [0, V) is skipped with r unchanged).  When no child is accepted (or cur is a leaf) the
+ *   walk ends and bonus_token[b] = the lowest v with sum_{w<=v} r[w] > u_resample[b] * sum_w r[w].
+ *   With children drawn independently from q the emitted tokens follow the target distribution.
+ *   path, accept_len, accepted_tokens, status, max_path: as in s4c_accept_path; bonus_token is
+ *   always a token id here (-1 only for a flagged sequence).
+ * Arithmetic is fp64 (row maxima exact).  V <= 2^21.  No workspace. */
+s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
+                               const void* logits, const float* draft_probs, const int32_t* parent,
+                               const int32_t* tokens, const float* uniforms, const float* u_resample,
+                               int32_t max_path, int32_t* path, int32_t* accept_len,
+                               int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                               void* hip_stream);
+
 /* KV reuse (Sec. 3.2, last paragraph): for k = 0 .. accept_len[b], tree row path[b][k] of every
  * KV head is copied to cache row cache_len[b] + k (K and V); then cache_len[b] += accept_len[b]+1.
  * Only shape->B, Hkv, D, N, S_cap, dtype are used.

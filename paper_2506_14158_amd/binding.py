@@ -19,7 +19,8 @@ S4C_GREEDY, S4C_STOCHASTIC = 0, 1
 S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
-           "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits")
+           "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
+           "s4c_accept_resample")
 
 
 class S4CError(RuntimeError):
@@ -56,6 +57,8 @@ def lib() -> C.CDLL:
         L.s4c_accept_path.restype = C.c_int
         L.s4c_accept_path.argtypes = [C.c_int32] * 5 + [C.c_float] + [C.c_void_p] * 5 + [C.c_int32] + [
             C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_accept_resample.restype = C.c_int
+        L.s4c_accept_resample.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 6 + [C.c_int32] + [C.c_void_p] * 6
         L.s4c_kv_compact.restype = C.c_int
         L.s4c_kv_compact.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 7 + [C.c_int32] + [C.c_void_p] * 3
         L.s4c_strerror.restype = C.c_char_p
@@ -153,6 +156,30 @@ def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, acce
                                  _ptr(parent), _ptr(tokens), _ptr(p_draft), _ptr(uniforms), int(max_path),
                                  _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
                                  _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+
+
+def s4c_accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resample, max_path: int, path,
+                        accept_len, accepted_tokens, bonus_token, temperature: float = 1.0,
+                        status: Optional[torch.Tensor] = None) -> None:
+    B, N, V = logits.shape
+    for t in (parent, tokens):
+        if t.dtype != torch.int32 or tuple(t.shape) != (B, N):
+            raise TypeError("parent / tokens must be int32 [B][N]")
+    if draft_probs.dtype != torch.float32 or tuple(draft_probs.shape) != (B, N, V):
+        raise TypeError("draft_probs must be float32 [B][N][V]")
+    if uniforms.dtype != torch.float32 or tuple(uniforms.shape) != (B, N):
+        raise TypeError("uniforms must be float32 [B][N]")
+    if u_resample.dtype != torch.float32 or tuple(u_resample.shape) != (B,):
+        raise TypeError("u_resample must be float32 [B]")
+    if tuple(path.shape) != (B, max_path) or tuple(accepted_tokens.shape) != (B, max_path):
+        raise ValueError("path / accepted_tokens must be [B][max_path]")
+    for t in (path, accept_len, accepted_tokens, bonus_token):
+        if t.dtype != torch.int32:
+            raise TypeError("outputs must be int32")
+    _check(lib().s4c_accept_resample(B, N, V, _dtype_code(logits), float(temperature), _ptr(logits), _ptr(draft_probs),
+                                     _ptr(parent), _ptr(tokens), _ptr(uniforms), _ptr(u_resample), int(max_path),
+                                     _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
+                                     _ptr(status), _stream()))
 
 
 def s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len,

@@ -81,6 +81,24 @@ struct AcceptArgs {
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
 int accept_chunk_elems();
 
+struct ResampleArgs {
+    const void* logits;
+    const float* draft;        // [B][N][V]
+    const int32_t* parent;
+    const int32_t* tokens;
+    const float* uniforms;     // [B][N]
+    const float* u_resample;   // [B]
+    int32_t* path;
+    int32_t* accept_len;
+    int32_t* accepted_tokens;
+    int32_t* bonus_token;
+    int32_t* status;
+    int32_t B, N, V, max_path, dtype;
+    double temperature;
+};
+hipError_t launch_accept_resample(const ResampleArgs& a, hipStream_t st);
+int resample_max_vocab();
+
 struct CompactArgs {
     const void* k_tree;
     const void* v_tree;

@@ -21,4 +21,7 @@ def to_device(cfg, parent, at=None, ac=None, device="cuda"):
         d["tokens"] = torch.from_numpy(ac.tokens).to(device)
         d["p_draft"] = torch.from_numpy(ac.p_draft).to(device)
         d["uniforms"] = torch.from_numpy(ac.uniforms).to(device)
+        if ac.draft_probs is not None:
+            d["draft_probs"] = torch.from_numpy(ac.draft_probs).to(device)
+            d["u_resample"] = torch.from_numpy(ac.u_resample).to(device)
     return d

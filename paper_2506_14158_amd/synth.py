@@ -29,6 +29,7 @@ BASE_SEED = 250614158
 # component ids for SeedSequence spawning (fixed, documented draw order)
 _C_TREE, _C_Q, _C_KTREE, _C_VTREE, _C_KCACHE, _C_VCACHE = 1, 2, 3, 4, 5, 6
 _C_LOGITS, _C_TOKENS, _C_PLANT, _C_DRAFT, _C_UNIF = 7, 8, 9, 10, 11
+_C_RESAMPLE = 12
 
 
 @dataclasses.dataclass(frozen=True)
@@ -238,6 +239,8 @@ class AcceptInputs:
     tokens: np.ndarray     # [B][N] int32
     p_draft: np.ndarray    # [B][N] float32 (stochastic; zeros in greedy)
     uniforms: np.ndarray   # [B][N] float32 in [0,1)
+    draft_probs: Optional[np.ndarray] = None   # [B][N][V] float32: row u = draft distribution at node u (full_draft)
+    u_resample: Optional[np.ndarray] = None    # [B] float32 in [0,1) for the correction token (full_draft)
 
 
 def _softmax64(x: np.ndarray) -> np.ndarray:
@@ -246,8 +249,16 @@ def _softmax64(x: np.ndarray) -> np.ndarray:
     return e / e.sum()
 
 
+def draw_u_resample(seed: int, B: int, attempt: int = 0) -> np.ndarray:
+    """[B] float32 uniforms for the correction token; attempt k re-draws them (test conditioning)."""
+    return np.array([_rng(seed, _C_RESAMPLE, b + 100_000 * attempt).random(dtype=np.float32) for b in range(B)],
+                    dtype=np.float32)
+
+
 def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int] = None,
-                       threads: int = 8) -> AcceptInputs:
+                       threads: int = 8, full_draft: bool = False) -> AcceptInputs:
+    """full_draft (stochastic mode only): also keep every internal node's whole draft
+    distribution and draw the uniforms of the correction token; the other arrays are unchanged."""
     seed = cfg.seed() if seed is None else seed
     st = np.float32 if cfg.dtype == "f32" else np.uint16
     B, N, V = cfg.B, cfg.N, cfg.V
@@ -255,6 +266,9 @@ def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int
     tokens = np.zeros((B, N), dtype=np.int32)
     p_draft = np.zeros((B, N), dtype=np.float32)
     uniforms = np.empty((B, N), dtype=np.float32)
+    if full_draft and cfg.mode != "stochastic":
+        raise ValueError("full_draft needs a stochastic config")
+    draft_probs = np.zeros((B, N, V), dtype=np.float32) if full_draft else None
 
     def one(b):
         logits[b] = _normal(seed, _C_LOGITS, b, (N, V), 2.0, cfg.dtype)
@@ -285,10 +299,13 @@ def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int
                 top = np.argsort(-pd, kind="stable")[:k]
                 tokens[b, ch[u]] = top.astype(np.int32)
                 p_draft[b, ch[u]] = pd[top].astype(np.float32)
+                if full_draft:
+                    draft_probs[b, u] = pd.astype(np.float32)
 
     with ThreadPoolExecutor(max_workers=max(1, min(threads, B))) as ex:
         list(ex.map(one, range(B)))
-    return AcceptInputs(logits, tokens, p_draft, uniforms)
+    return AcceptInputs(logits, tokens, p_draft, uniforms, draft_probs,
+                        draw_u_resample(seed, B) if full_draft else None)
 
 
 def levels_of(parent_row: np.ndarray) -> np.ndarray:

@@ -41,6 +41,12 @@ class TreeVerifier:
                            self.accepted_tokens, self.bonus_token, self.accept_ws, p_draft, uniforms,
                            temperature, self.accept_status)
 
+    def accept_resample(self, logits, draft_probs, parent, tokens, uniforms, u_resample, temperature=1.0):
+        """Sibling-sequential rule with the correction token; same outputs as accept_path."""
+        _b.s4c_accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resample, self.max_path, self.path,
+                               self.accept_len, self.accepted_tokens, self.bonus_token, temperature,
+                               self.accept_status)
+
     def kv_compact(self, k_tree, v_tree, k_cache, v_cache, cache_len):
         _b.s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, self.path, self.accept_len,
                           self.dst_index, self.compact_status)

@@ -30,3 +30,22 @@ def accept_inputs_with_margin(cfg, parent, oracle_mod, max_tries=8):
         if cfg.mode == "greedy" or float(r["margin"].min()) > MARGIN_MIN:
             return ac, r
     raise RuntimeError("no well-conditioned seed found")
+
+
+RESAMPLE_MARGIN_MIN = 1e-9   # fp64 on both sides: sums of <= 2^21 terms differ by ~1e-13 relative
+
+
+def resample_inputs_with_margin(cfg, parent, oracle_mod, max_tries=8):
+    """Sequential rule with the correction token: the GPU and the oracle both work in fp64 but add
+    in different orders, so a decision closer to equality than RESAMPLE_MARGIN_MIN (relative) is
+    not comparable.  The correction token's uniform is re-drawn for such a case (expected about
+    once in 10^4 sequences); an accept test that close fails the workload."""
+    ac = synth.make_accept_inputs(cfg, parent, full_draft=True)
+    for k in range(max_tries):
+        r = oracle_mod.accept_resample(ac.logits, ac.draft_probs, parent, ac.tokens, ac.uniforms, ac.u_resample,
+                                       cfg.levels, cfg.temperature)
+        assert float(r["margin_accept"].min()) > RESAMPLE_MARGIN_MIN
+        if float(r["margin_sample"][r["status"] == 0].min(initial=1.0)) > RESAMPLE_MARGIN_MIN:
+            return ac, r
+        ac.u_resample = synth.draw_u_resample(cfg.seed(), cfg.B, attempt=k + 1)
+    raise RuntimeError("no well-conditioned correction-token uniforms found")
