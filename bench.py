@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="1..5 (BASELINE configs); 5 is the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="re-use one input copy every step (cache-warm numbers)")
+    ap.add_argument("--resample", action="store_true",
+                    help="also time s4c_accept_resample (sequential rule with the correction token; stochastic "
+                         "configs only; reported as accept_resample, not part of the step)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -94,7 +97,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     par = synth.make_parent(cfg)
     at = synth.make_attn_inputs(cfg, threads=16)
-    ac = synth.make_accept_inputs(cfg, par, threads=16)
+    resample = args.resample and cfg.mode == "stochastic"
+    ac = synth.make_accept_inputs(cfg, par, threads=16, full_draft=resample)
     d0 = to_device(cfg, par, at, ac)
     in_bytes = sum(v.numel() * v.element_size() for v in d0.values())
     ncopy = 1 if args.warm else int(max(1, min(64, -(-(1 << 30) // in_bytes))))
@@ -182,6 +186,22 @@ def main():
         "accept_path_GBps": logits_bytes / t_acc / 1e9,
         "paper_context": "paper reports 2.26x-2.60x end-to-end vs autoregressive decoding (A100-40GB / 4xRTX4090, fp16, batch 1)",
     }
+    if resample:
+        d = copies[0]
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for k in range(args.warmup + args.steps):
+            e = evs[k - args.warmup] if k >= args.warmup else None
+            if e:
+                e[0].record()
+            tv.accept_resample(d["logits"], d["draft_probs"], d["parent"], d["tokens"], d["uniforms"], d["u_resample"],
+                               cfg.temperature)
+            if e:
+                e[1].record()
+        torch.cuda.synchronize()
+        ms = np.array([a.elapsed_time(b) for a, b in evs])
+        L = tv.accept_len.cpu().numpy()
+        rec["accept_resample"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "dtype": "f64",
+                                  "accept_len_mean": float(L.mean()), "accept_len_max": int(L.max())}
     if args.graph:
         # launch-bound configs: one graph launch instead of six kernel launches per step
         side = torch.cuda.Stream()

@@ -47,6 +47,9 @@ typedef enum { S4C_GREEDY = 0, S4C_STOCHASTIC = 1 } s4c_accept_mode;
 /* bits of the per-sequence device status word */
 #define S4C_SEQ_BAD_TREE 1     /* parent[] is not a valid tree / path deeper than max_path */
 #define S4C_SEQ_BAD_LEN  2     /* cache_len out of range / accepted rows do not fit S_cap */
+#define S4C_SEQ_TIMEOUT  4     /* s4c_accept_resample: the workgroups of a sequence could not exchange
+                                  their partial sums within the poll limit (GPU shared with a kernel
+                                  that never ends); accept_len = 0, bonus = -1 */
 
 typedef struct {
     int32_t B;       /* sequences */
@@ -132,13 +135,19 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
  *   With children drawn independently from q the emitted tokens follow the target distribution.
  *   path, accept_len, accepted_tokens, status, max_path: as in s4c_accept_path; bonus_token is
  *   always a token id here (-1 only for a flagged sequence).
- * Arithmetic is fp64 (row maxima exact).  V <= 2^21.  No workspace. */
+ *   workspace  >= s4c_accept_resample_workspace_size(B, N, V, max_path) bytes, 256-byte aligned,
+ *              contents need not be initialised; may be NULL if that size is 0.  It carries the
+ *              partial sums that the workgroups sharing one sequence exchange, so two calls that
+ *              may overlap in time must not share it.
+ * Arithmetic is fp64 (row maxima exact).  V <= 2^21.  The kernel polls device memory with a
+ * bounded number of tries (S4C_SEQ_TIMEOUT); it needs at most 256 workgroups resident at once. */
+size_t s4c_accept_resample_workspace_size(int32_t B, int32_t N, int32_t V, int32_t max_path);
 s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
                                const void* logits, const float* draft_probs, const int32_t* parent,
                                const int32_t* tokens, const float* uniforms, const float* u_resample,
                                int32_t max_path, int32_t* path, int32_t* accept_len,
                                int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
-                               void* hip_stream);
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* KV reuse (Sec. 3.2, last paragraph): for k = 0 .. accept_len[b], tree row path[b][k] of every
  * KV head is copied to cache row cache_len[b] + k (K and V); then cache_len[b] += accept_len[b]+1.

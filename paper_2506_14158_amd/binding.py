@@ -20,7 +20,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
-           "s4c_accept_resample")
+           "s4c_accept_resample", "s4c_accept_resample_workspace_size")
 
 
 class S4CError(RuntimeError):
@@ -58,7 +58,10 @@ def lib() -> C.CDLL:
         L.s4c_accept_path.argtypes = [C.c_int32] * 5 + [C.c_float] + [C.c_void_p] * 5 + [C.c_int32] + [
             C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         L.s4c_accept_resample.restype = C.c_int
-        L.s4c_accept_resample.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 6 + [C.c_int32] + [C.c_void_p] * 6
+        L.s4c_accept_resample.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 6 + [C.c_int32] + [
+            C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_accept_resample_workspace_size.restype = C.c_size_t
+        L.s4c_accept_resample_workspace_size.argtypes = [C.c_int32] * 4
         L.s4c_kv_compact.restype = C.c_int
         L.s4c_kv_compact.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 7 + [C.c_int32] + [C.c_void_p] * 3
         L.s4c_strerror.restype = C.c_char_p
@@ -158,8 +161,12 @@ def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, acce
                                  _ptr(status), _ptr(workspace), ws_bytes, _stream()))
 
 
+def s4c_accept_resample_workspace_size(B: int, N: int, V: int, max_path: int) -> int:
+    return int(lib().s4c_accept_resample_workspace_size(B, N, V, max_path))
+
+
 def s4c_accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resample, max_path: int, path,
-                        accept_len, accepted_tokens, bonus_token, temperature: float = 1.0,
+                        accept_len, accepted_tokens, bonus_token, workspace=None, temperature: float = 1.0,
                         status: Optional[torch.Tensor] = None) -> None:
     B, N, V = logits.shape
     for t in (parent, tokens):
@@ -179,7 +186,9 @@ def s4c_accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resampl
     _check(lib().s4c_accept_resample(B, N, V, _dtype_code(logits), float(temperature), _ptr(logits), _ptr(draft_probs),
                                      _ptr(parent), _ptr(tokens), _ptr(uniforms), _ptr(u_resample), int(max_path),
                                      _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
-                                     _ptr(status), _stream()))
+                                     _ptr(status), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                     _stream()))
 
 
 def s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len,

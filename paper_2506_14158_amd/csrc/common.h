@@ -93,11 +93,17 @@ struct ResampleArgs {
     int32_t* accepted_tokens;
     int32_t* bonus_token;
     int32_t* status;
+    uint64_t* slots;           // [B][max_pass][2][team] exchange words (team > 1)
     int32_t B, N, V, max_path, dtype;
+    int32_t team;              // workgroups per sequence
+    int32_t max_pass;          // exchanges a sequence may need
     double temperature;
 };
 hipError_t launch_accept_resample(const ResampleArgs& a, hipStream_t st);
 int resample_max_vocab();
+int resample_team(int B, int V);
+int resample_max_pass(int N, int max_path);
+size_t resample_slot_words(int B, int N, int V, int max_path);
 
 struct CompactArgs {
     const void* k_tree;

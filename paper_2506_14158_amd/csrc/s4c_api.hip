@@ -173,23 +173,32 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+size_t s4c_accept_resample_workspace_size(int32_t B, int32_t N, int32_t V, int32_t max_path) {
+    if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0 || N > kMaxNodes || V > resample_max_vocab()) return 0;
+    return resample_slot_words(B, N, V, max_path) * sizeof(uint64_t);
+}
+
 s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
                                const void* logits, const float* draft_probs, const int32_t* parent,
                                const int32_t* tokens, const float* uniforms, const float* u_resample,
                                int32_t max_path, int32_t* path, int32_t* accept_len,
                                int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
-                               void* hip_stream) {
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!logits || !draft_probs || !parent || !tokens || !uniforms || !u_resample || !path || !accept_len ||
         !accepted_tokens || !bonus_token)
         return S4C_ERR_NULL;
     if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0 || !(temperature > 0.f)) return S4C_ERR_SHAPE;
     if (N > kMaxNodes || V > resample_max_vocab() || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16))
         return S4C_ERR_UNSUPPORTED;
+    const size_t need = s4c_accept_resample_workspace_size(B, N, V, max_path);
+    if (need > 0 && (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255))) return S4C_ERR_WORKSPACE;
     ResampleArgs a;
     a.logits = logits; a.draft = draft_probs; a.parent = parent; a.tokens = tokens; a.uniforms = uniforms;
     a.u_resample = u_resample; a.path = path; a.accept_len = accept_len; a.accepted_tokens = accepted_tokens;
-    a.bonus_token = bonus_token; a.status = status;
+    a.bonus_token = bonus_token; a.status = status; a.slots = (uint64_t*)workspace;
     a.B = B; a.N = N; a.V = V; a.max_path = max_path; a.dtype = logits_dtype; a.temperature = (double)temperature;
+    a.team = resample_team(B, V);
+    a.max_pass = resample_max_pass(N, max_path);
     return launch_accept_resample(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 

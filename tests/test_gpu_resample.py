@@ -140,6 +140,10 @@ def test_rejects_bad_arguments():
     with pytest.raises(B.S4CError):      # temperature must be positive
         B.s4c_accept_resample(t(1, 2, 8), t(1, 2, 8), i(1, 2), i(1, 2), t(1, 2), t(1), 2, i(1, 2), i(1), i(1, 2), i(1),
                               temperature=0.0)
+    with pytest.raises(B.S4CError):      # a team of workgroups needs its exchange workspace
+        assert B.s4c_accept_resample_workspace_size(2, 3, 40000, 3) > 0
+        B.s4c_accept_resample(t(2, 3, 40000), t(2, 3, 40000), i(2, 3), i(2, 3), t(2, 3), t(2), 3, i(2, 3), i(2), i(2, 3),
+                              i(2), workspace=None)
     with pytest.raises(B.S4CError):      # more nodes than a tree may hold
         B.s4c_accept_resample(t(1, 129, 8), t(1, 129, 8), i(1, 129), i(1, 129), t(1, 129), t(1), 2, i(1, 2), i(1),
                               i(1, 2), i(1))
