@@ -399,3 +399,40 @@ int oracle_kv_compact(const oracle_shape* s, const void* k_tree, const void* v_t
     }
     return 0;
 }
+
+int oracle_commit_path(const oracle_shape* s, int32_t layers, const void* k_tree, const void* v_tree,
+                       void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                       const int32_t* accept_len, int32_t max_path, const void* features,
+                       int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status) {
+    const size_t es = elem_size(s->dtype);
+    const size_t row = (size_t)s->D * es;
+    const size_t tree_layer = (size_t)s->B * s->N * s->Hkv * row;
+    const size_t cache_layer = (size_t)s->B * s->Hkv * s->S_cap * row;
+    for (int32_t b = 0; b < s->B; ++b) {
+        const int32_t L = accept_len[b];
+        const int32_t base = cache_len[b];
+        const int32_t* pth = path + (size_t)b * max_path;
+        if (dst_index)
+            for (int32_t k = 0; k < max_path; ++k) dst_index[(size_t)b * max_path + k] = -1;
+        int bad = (L < 0 || L >= max_path || base < 0 || (int64_t)base + L + 1 > s->S_cap);
+        for (int32_t k = 0; !bad && k <= L; ++k)
+            if (pth[k] < 0 || pth[k] >= s->N) bad = 1;
+        if (status) status[b] = bad ? ORACLE_BAD_LEN : 0;
+        if (bad) continue;
+        for (int32_t k = 0; k <= L; ++k) {
+            for (int32_t l = 0; l < layers; ++l)
+                for (int32_t h = 0; h < s->Hkv; ++h) {
+                    const size_t src = l * tree_layer + (((size_t)b * s->N + pth[k]) * s->Hkv + h) * row;
+                    const size_t dst = l * cache_layer + (((size_t)b * s->Hkv + h) * s->S_cap + (size_t)(base + k)) * row;
+                    memcpy((char*)k_cache + dst, (const char*)k_tree + src, row);
+                    memcpy((char*)v_cache + dst, (const char*)v_tree + src, row);
+                }
+            if (features && features_out)
+                memcpy((char*)features_out + ((size_t)b * max_path + k) * feature_bytes,
+                       (const char*)features + ((size_t)b * s->N + pth[k]) * feature_bytes, (size_t)feature_bytes);
+            if (dst_index) dst_index[(size_t)b * max_path + k] = base + k;
+        }
+        cache_len[b] = base + L + 1;
+    }
+    return 0;
+}

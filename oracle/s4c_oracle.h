@@ -108,6 +108,17 @@ int oracle_kv_compact(const oracle_shape* s, const void* k_tree, const void* v_t
                       const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
                       int32_t* status);
 
+/* The same for a whole model in one call (Sec. 3.2, last paragraph: the accepted tokens and
+ * their features are kept for the next drafting phase): k_tree, v_tree are [layers][B][N][Hkv][D],
+ * k_cache, v_cache [layers][B][Hkv][S_cap][D]; cache_len [B] is shared by the layers and advanced
+ * once.  If features (bytes [B][N][feature_bytes]) and features_out ([B][max_path][feature_bytes])
+ * are given, features_out[b][k] = features[b][path[b][k]] for k = 0..accept_len[b]; other rows of
+ * features_out are left as they were.  A flagged sequence (status bit 2) is untouched everywhere. */
+int oracle_commit_path(const oracle_shape* s, int32_t layers, const void* k_tree, const void* v_tree,
+                       void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                       const int32_t* accept_len, int32_t max_path, const void* features,
+                       int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status);
+
 int oracle_num_threads(void);
 
 #ifdef __cplusplus

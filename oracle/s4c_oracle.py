@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -174,5 +174,30 @@ def kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len):
     status = np.zeros(B, dtype=np.int32)
     rc = lib.oracle_kv_compact(C.byref(s), _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache), _p(cache_len),
                                _p(path), _p(accept_len), C.c_int32(max_path), _p(dst), _p(status))
+    assert rc == 0
+    return dst, status
+
+
+def commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len, features=None, features_out=None):
+    """Multi-layer compaction, in place on k_cache, v_cache [layers][B][Hkv][S_cap][D], cache_len and
+    features_out ([B][max_path][F], any dtype) -> (dst_index, status)"""
+    lib = _load()
+    Ly, B, N, Hkv, D = k_tree.shape
+    S_cap = k_cache.shape[3]
+    assert k_cache.shape == (Ly, B, Hkv, S_cap, D) and v_tree.shape == k_tree.shape and v_cache.shape == k_cache.shape
+    s = _Shape(B, Hkv, Hkv, D, N, S_cap, _dt(k_tree))
+    assert cache_len.dtype == np.int32 and cache_len.flags["C_CONTIGUOUS"]
+    path, accept_len = _i32(path), _i32(accept_len)
+    max_path = path.shape[1]
+    fb = 0
+    if features is not None:
+        assert features.shape[:2] == (B, N) and features_out.shape[:2] == (B, max_path)
+        fb = int(features[0, 0].nbytes)
+        assert int(features_out[0, 0].nbytes) == fb
+    dst = np.empty((B, max_path), dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_commit_path(C.byref(s), C.c_int32(Ly), _p(k_tree), _p(v_tree), _p(k_cache), _p(v_cache),
+                                _p(cache_len), _p(path), _p(accept_len), C.c_int32(max_path), _p(features),
+                                C.c_int32(fb), _p(features_out), _p(dst), _p(status))
     assert rc == 0
     return dst, status

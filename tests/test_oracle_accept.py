@@ -250,3 +250,37 @@ def test_generated_workloads_have_the_stated_structure():
     np.testing.assert_array_equal(acc.logits, a2.logits)                           # seeded => reproducible
     r = O.accept_path(acc.logits, par, acc.tokens, "stochastic", small.levels, acc.p_draft, acc.uniforms)
     assert (r["status"] == 0).all()
+
+
+# ------------------------------------------------------------------------------ multi-layer commit
+def test_commit_path_equals_per_layer_compaction_and_feature_gather():
+    """All layers in one call == the single-layer routine applied layer by layer from the same
+    cache_len, and the feature rows == a plain numpy gather of the path's nodes."""
+    rng = np.random.default_rng(17)
+    Ly, B, N, Hkv, D, P, mp, F = 3, 4, 9, 2, 8, 5, 5, 6
+    S_cap = P + 4                                                    # sequence 3 overflows
+    kt = rng.standard_normal((Ly, B, N, Hkv, D)).astype(np.float32)
+    vt = rng.standard_normal((Ly, B, N, Hkv, D)).astype(np.float32)
+    kc = rng.standard_normal((Ly, B, Hkv, S_cap, D)).astype(np.float32)
+    vc = rng.standard_normal((Ly, B, Hkv, S_cap, D)).astype(np.float32)
+    cl = np.array([P, P - 2, 0, P], dtype=np.int32)
+    path = np.array([[0, 2, 5, -1, -1], [0, -1, -1, -1, -1], [0, 1, 3, 7, -1], [0, 1, 4, 6, 8]], dtype=np.int32)
+    alen = np.array([2, 0, 3, 4], dtype=np.int32)
+    feats = rng.standard_normal((B, N, F)).astype(np.float32)
+    fout = np.full((B, mp, F), -5.0, dtype=np.float32)
+    kc1, vc1, cl1, fout1 = kc.copy(), vc.copy(), cl.copy(), fout.copy()
+    dst, st = O.commit_path(kt, vt, kc1, vc1, cl1, path, alen, feats, fout1)
+    assert st.tolist() == [0, 0, 0, 2]
+    for l in range(Ly):
+        kcl, vcl, cll = kc[l].copy(), vc[l].copy(), cl.copy()
+        d2, s2 = O.kv_compact(kt[l], vt[l], kcl, vcl, cll, path, alen)
+        assert np.array_equal(kcl, kc1[l]) and np.array_equal(vcl, vc1[l])
+        assert np.array_equal(cll, cl1) and np.array_equal(d2, dst) and np.array_equal(s2, st)
+    want = fout.copy()
+    for b in range(3):
+        want[b, :alen[b] + 1] = feats[b, path[b, :alen[b] + 1]]
+    assert np.array_equal(fout1, want)                               # flagged sequence 3 and padding rows untouched
+    # no features: same caches
+    kc2, vc2, cl2 = kc.copy(), vc.copy(), cl.copy()
+    O.commit_path(kt, vt, kc2, vc2, cl2, path, alen)
+    assert np.array_equal(kc2, kc1) and np.array_equal(cl2, cl1)
