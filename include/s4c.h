@@ -160,6 +160,23 @@ s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const
                           const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
                           int32_t* status, void* hip_stream);
 
+/* The same for every layer of a model in one call, plus the accepted nodes' feature rows (Sec. 3.2,
+ * last paragraph: the accepted tokens and their features are kept for the next drafting phase).
+ *   k_tree, v_tree   [layers][B][N][Hkv][D]        k_cache, v_cache [layers][B][Hkv][S_cap][D]
+ *   cache_len [B] is shared by the layers and advanced once, after all rows were copied.
+ *   features      [B][N][feature_bytes] (bytes of any element type; the penultimate-layer
+ *                 output of every tree node), nullable together with
+ *   features_out  [B][max_path][feature_bytes]: row k receives the feature row of node path[b][k]
+ *                 for k = 0 .. accept_len[b]; other rows are left as they were.
+ *                 feature_bytes is a positive multiple of 16, both pointers 16-byte aligned.
+ *   dst_index, status, max_path: as in s4c_kv_compact; a flagged sequence is untouched in every
+ *   layer and in features_out.  1 <= layers <= 65534. */
+s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                           void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                           const int32_t* accept_len, int32_t max_path, const void* features,
+                           int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
+                           void* hip_stream);
+
 /* Static, never NULL. */
 const char* s4c_strerror(s4c_status code);
 

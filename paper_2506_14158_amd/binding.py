@@ -20,7 +20,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
-           "s4c_accept_resample", "s4c_accept_resample_workspace_size")
+           "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path")
 
 
 class S4CError(RuntimeError):
@@ -64,6 +64,9 @@ def lib() -> C.CDLL:
         L.s4c_accept_resample_workspace_size.argtypes = [C.c_int32] * 4
         L.s4c_kv_compact.restype = C.c_int
         L.s4c_kv_compact.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 7 + [C.c_int32] + [C.c_void_p] * 3
+        L.s4c_commit_path.restype = C.c_int
+        L.s4c_commit_path.argtypes = [C.POINTER(AttnShape), C.c_int32] + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p,
+                                                                                          C.c_int32] + [C.c_void_p] * 4
         L.s4c_strerror.restype = C.c_char_p
         L.s4c_strerror.argtypes = [C.c_int]
         _lib = L
@@ -203,6 +206,31 @@ def s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len
     _check(lib().s4c_kv_compact(C.byref(shape), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
                                 _ptr(cache_len), _ptr(path), _ptr(accept_len), int(path.shape[1]),
                                 _ptr(dst_index), _ptr(status), _stream()))
+
+
+def s4c_commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len, features=None, features_out=None,
+                    dst_index: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> None:
+    """k_tree/v_tree [layers][B][N][Hkv][D], caches [layers][B][Hkv][S_cap][D]; features [B][N][F] -> features_out
+    [B][max_path][F] (same dtype)."""
+    Ly, B, N, Hkv, D = k_tree.shape
+    S_cap = k_cache.shape[3]
+    if tuple(k_cache.shape) != (Ly, B, Hkv, S_cap, D) or v_tree.shape != k_tree.shape or v_cache.shape != k_cache.shape:
+        raise ValueError("inconsistent shapes")
+    if cache_len.dtype != torch.int32 or path.dtype != torch.int32 or accept_len.dtype != torch.int32:
+        raise TypeError("cache_len / path / accept_len must be int32")
+    max_path = int(path.shape[1])
+    fb = 0
+    if features is not None or features_out is not None:
+        if features is None or features_out is None or features.dtype != features_out.dtype:
+            raise TypeError("features and features_out go together and share a dtype")
+        if tuple(features.shape[:2]) != (B, N) or tuple(features_out.shape[:2]) != (B, max_path) or \
+                features.shape[2:] != features_out.shape[2:]:
+            raise ValueError("features [B][N][F] / features_out [B][max_path][F]")
+        fb = int(features[0, 0].numel() * features.element_size())
+    shape = AttnShape(B, Hkv, Hkv, D, N, S_cap, _dtype_code(k_tree))
+    _check(lib().s4c_commit_path(C.byref(shape), int(Ly), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
+                                 _ptr(cache_len), _ptr(path), _ptr(accept_len), max_path, _ptr(features), fb,
+                                 _ptr(features_out), _ptr(dst_index), _ptr(status), _stream()))
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:

@@ -120,4 +120,23 @@ struct CompactArgs {
 };
 hipError_t launch_compact(const CompactArgs& a, hipStream_t st);
 
+struct CommitArgs {
+    const void* k_tree;        // [layers][B][N][Hkv][D]
+    const void* v_tree;
+    void* k_cache;             // [layers][B][Hkv][S_cap][D]
+    void* v_cache;
+    int32_t* cache_len;
+    const int32_t* path;
+    const int32_t* accept_len;
+    const void* features;      // [B][N][feature_bytes] or null
+    void* features_out;        // [B][max_path][feature_bytes] or null
+    int32_t* dst_index;
+    int32_t* status;
+    size_t tree_layer_bytes, cache_layer_bytes;
+    int32_t B, Hkv, N, S_cap, max_path, layers;
+    int32_t row_bytes;         // D * element size
+    int32_t feature_bytes;
+};
+hipError_t launch_commit(const CommitArgs& a, hipStream_t st);
+
 }  // namespace s4c

@@ -223,5 +223,36 @@ s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const
     return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                           void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                           const int32_t* accept_len, int32_t max_path, const void* features,
+                           int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
+                           void* hip_stream) {
+    if (!shape || !k_tree || !v_tree || !k_cache || !v_cache || !cache_len || !path || !accept_len)
+        return S4C_ERR_NULL;
+    s4c_attn_shape s = *shape;
+    if (s.Hq <= 0) s.Hq = s.Hkv;          // Hq is not used by this call
+    if (s.Hkv > 0 && s.Hq % s.Hkv != 0) s.Hq = s.Hkv;
+    s4c_status why;
+    if (!shape_ok(&s, &why)) return why;
+    if (max_path <= 0 || s.S_cap <= 0 || layers <= 0 || layers > 65534) return S4C_ERR_SHAPE;
+    const bool feats = features || features_out;
+    if (feats) {
+        if (!features || !features_out) return S4C_ERR_NULL;
+        if (feature_bytes <= 0 || feature_bytes % 16 != 0) return S4C_ERR_SHAPE;
+        if ((((uintptr_t)features) | ((uintptr_t)features_out)) & 15) return S4C_ERR_SHAPE;
+    }
+    CommitArgs a;
+    a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache; a.cache_len = cache_len;
+    a.path = path; a.accept_len = accept_len; a.features = features; a.features_out = features_out;
+    a.dst_index = dst_index; a.status = status;
+    a.B = s.B; a.Hkv = s.Hkv; a.N = s.N; a.S_cap = s.S_cap; a.max_path = max_path; a.layers = layers;
+    a.row_bytes = s.D * (s.dtype == S4C_F32 ? 4 : 2);
+    a.feature_bytes = feats ? feature_bytes : 0;
+    a.tree_layer_bytes = (size_t)s.B * s.N * s.Hkv * a.row_bytes;
+    a.cache_layer_bytes = (size_t)s.B * s.Hkv * s.S_cap * a.row_bytes;
+    return launch_commit(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -55,6 +55,11 @@ class TreeVerifier:
         _b.s4c_kv_compact(k_tree, v_tree, k_cache, v_cache, cache_len, self.path, self.accept_len,
                           self.dst_index, self.compact_status)
 
+    def commit_path(self, k_tree, v_tree, k_cache, v_cache, cache_len, features=None, features_out=None):
+        """All layers' K/V rows (leading [layers] dimension) and the feature rows of the accepted path."""
+        _b.s4c_commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, self.path, self.accept_len, features,
+                           features_out, self.dst_index, self.compact_status)
+
     def step(self, q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, logits, tokens, mode: int,
              p_draft=None, uniforms=None, temperature: float = 1.0, scale: float = 0.0):
         self.tree_attn(q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, scale)
