@@ -78,6 +78,10 @@ def main():
     ap.add_argument("--resample", action="store_true",
                     help="also time s4c_accept_resample (sequential rule with the correction token; stochastic "
                          "configs only; reported as accept_resample, not part of the step)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="also time a whole-model verify: this many layers of tree attention (each with its own KV "
+                         "cache), one acceptance, one s4c_commit_path over all layers + feature rows (reported as "
+                         "multi_layer, not part of the step)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -202,6 +206,40 @@ def main():
         L = tv.accept_len.cpu().numpy()
         rec["accept_resample"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "dtype": "f64",
                                   "accept_len_mean": float(L.mean()), "accept_len_max": int(L.max())}
+    if args.layers > 0:
+        # every layer gets its own K/V cache and tree K/V (device copies of the same synthetic layer)
+        Ly, d = args.layers, copies[0]
+        rep = lambda t: t.unsqueeze(0).repeat(Ly, *([1] * t.dim())).contiguous()
+        kcL, vcL, ktL, vtL = rep(d["k_cache"]), rep(d["v_cache"]), rep(d["k_tree"]), rep(d["v_tree"])
+        hidden = cfg.Hq * cfg.D
+        feats = torch.randn(cfg.B, cfg.N, hidden, device="cuda").to(d["q"].dtype)
+        fout = torch.zeros(cfg.B, cfg.levels, hidden, device="cuda", dtype=d["q"].dtype)
+
+        def model_step():
+            d["cache_len"].copy_(cache_len0)
+            for l in range(Ly):
+                tv.tree_attn(d["q"], ktL[l], vtL[l], kcL[l], vcL[l], d["cache_len"], d["parent"])
+            tv.accept_path(d["logits"], d["parent"], d["tokens"], mode, d["p_draft"], d["uniforms"], cfg.temperature)
+            tv.commit_path(ktL, vtL, kcL, vcL, d["cache_len"], feats, fout)
+
+        nsteps = max(2, min(args.steps, 10))
+        model_step()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t0 = time.perf_counter()
+        for k in range(nsteps):
+            model_step()
+        torch.cuda.synchronize()
+        ms_model = (time.perf_counter() - t0) * 1e3 / nsteps
+        d["cache_len"].copy_(cache_len0)
+        ev[0].record()
+        tv.commit_path(ktL, vtL, kcL, vcL, d["cache_len"], feats, fout)
+        ev[1].record()
+        torch.cuda.synchronize()
+        rec["multi_layer"] = {"layers": Ly, "ms_per_step": ms_model, "steps_per_s": 1e3 / ms_model,
+                              "commit_path_ms": ev[0].elapsed_time(ev[1]),
+                              "kv_cache_GB": 2 * kcL.numel() * kcL.element_size() / 1e9}
+        del kcL, vcL, ktL, vtL
     if args.graph:
         # launch-bound configs: one graph launch instead of six kernel launches per step
         side = torch.cuda.Stream()
