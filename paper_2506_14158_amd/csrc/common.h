@@ -75,7 +75,7 @@ struct AcceptArgs {
     float* ws_max;     // [B*N][chunks]
     int32_t* ws_arg;   // [B*N][chunks]
     float* ws_sum;     // [B*N][chunks]
-    int32_t B, N, V, chunks, chunk_elems, max_path, mode, dtype;
+    int32_t B, N, V, chunks, max_path, mode, dtype;
     float inv_temp_log2;   // log2(e) / T
 };
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);

@@ -40,9 +40,11 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
     // Balance unit: the 256 CUs for the matrix-core kernels (HBM- or MFMA-bound: what counts is
     // an equal share of work per CU), four workgroups per CU for the scalar kernel.  Split the prefix so that the launch fills
     // whole rounds of the 256 CUs without paying for more partial results than that needs:
-    // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), at least 128 keys per split.
+    // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), at least 128 keys per split
+    // (32, its key tile, for the scalar kernel, whose launches are latency-bound).
     const long slots = 256 * (p.mfma ? 1 : 4);
-    long max_splits = max_cache_len / 128;
+    const long gran = p.mfma ? 128 : 32;
+    long max_splits = max_cache_len / gran;
     if (max_splits > 16) max_splits = 16;
     if (max_splits < 1) max_splits = 1;
     long splits = 1;
@@ -53,8 +55,8 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
         if (cost < best - 1e-9) { best = cost; splits = sp; }
     }
     long chunk = (max_cache_len + splits - 1) / splits;
-    chunk = ((chunk + 127) / 128) * 128;
-    if (chunk < 128) chunk = 128;
+    chunk = ((chunk + gran - 1) / gran) * gran;
+    if (chunk < gran) chunk = gran;
     splits = (max_cache_len + chunk - 1) / chunk;
     if (splits < 1) splits = 1;
     p.splits = (int)splits;
@@ -167,7 +169,7 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     a.ws_max = (float*)workspace;
     a.ws_arg = (int32_t*)((char*)workspace + per);
     a.ws_sum = (float*)((char*)workspace + 2 * per);
-    a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)chunks; a.chunk_elems = accept_chunk_elems();
+    a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)chunks;
     a.max_path = max_path; a.mode = mode; a.dtype = logits_dtype;
     a.inv_temp_log2 = kLog2e / (mode == S4C_STOCHASTIC ? temperature : 1.0f);
     return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
