@@ -436,3 +436,66 @@ int oracle_commit_path(const oracle_shape* s, int32_t layers, const void* k_tree
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ tree construction */
+
+int oracle_build_tree(int32_t B, int32_t N, int32_t V, int32_t dtype, double temperature,
+                      const void* draft_logits, const int32_t* nchild, const int32_t* root_token,
+                      int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
+                      int32_t* status) {
+    if (N < 1 || V < 1 || kmax < 1 || temperature <= 0.0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t* nc = nchild + (size_t)b * N;
+        int32_t* par = parent + (size_t)b * N;
+        int32_t* tok = tokens + (size_t)b * N;
+        float* pd = p_draft + (size_t)b * N;
+        int32_t* lev = level ? level + (size_t)b * N : NULL;
+        for (int32_t i = 0; i < N; ++i) { par[i] = -1; tok[i] = -1; pd[i] = 0.f; if (lev) lev[i] = 0; }
+        tok[0] = root_token[b];
+        /* nodes are numbered level by level: node i's children are the next nchild[i] unused numbers;
+         * node i (i >= 1) must itself have been handed out before it can be a parent */
+        int bad = 0;
+        int64_t cum = 0;
+        for (int32_t i = 0; i < N && !bad; ++i) {
+            if (i >= 1 && cum < i) bad = 1;
+            if (nc[i] < 0 || nc[i] > kmax) bad = 1;
+            cum += nc[i] > 0 ? nc[i] : 0;
+        }
+        if (cum != N - 1) bad = 1;
+        if (status) status[b] = bad ? ORACLE_BAD_TREE : 0;
+        if (bad) continue;
+
+        char* taken = (char*)malloc((size_t)V);
+        int32_t next = 1;
+        for (int32_t i = 0; i < N; ++i) {
+            const int32_t k = nc[i];
+            if (k == 0) continue;
+            const size_t off = ((size_t)b * N + i) * V;
+            int32_t g;
+            double m, S;
+            row_stats_one(draft_logits, dtype, off, V, temperature, &g, &m, &S);
+            memset(taken, 0, (size_t)V);
+            for (int32_t r = 0; r < k; ++r) {
+                /* r-th candidate: the largest remaining logit, lowest token id among equals */
+                int32_t best = -1;
+                double bv = 0.0;
+                for (int32_t v = 0; v < V; ++v) {
+                    if (taken[v]) continue;
+                    const double x = load_elem(draft_logits, dtype, off + v);
+                    if (best < 0 || x > bv) { best = v; bv = x; }
+                }
+                const int32_t c = next++;
+                par[c] = i;
+                if (lev) lev[c] = lev[i] + 1;
+                if (best >= 0) {
+                    taken[best] = 1;
+                    tok[c] = best;
+                    pd[c] = (float)(exp((bv - m) / temperature) / S);
+                }
+            }
+        }
+        free(taken);
+    }
+    return 0;
+}

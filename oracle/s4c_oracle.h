@@ -119,6 +119,22 @@ int oracle_commit_path(const oracle_shape* s, int32_t layers, const void* k_tree
                        const int32_t* accept_len, int32_t max_path, const void* features,
                        int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status);
 
+/* Candidate tree from the drafter's distributions (Sec. 3.2: the top-1 continuation is drafted
+ * first, the next most probable tokens are added beside it as alternatives at the same position).
+ *   draft_logits [B][N][V]: row i = drafter's logits for the token after node i (rows of nodes
+ *                 without children are not read);  nchild [B][N]: children of node i, 0..kmax.
+ *   Nodes are numbered level by level: node i's children take the next nchild[i] unused numbers,
+ *   in order of decreasing draft probability (rank 0 = the top-1 token; equal logits: lowest
+ *   token id first).  Output: parent [B][N] (parent[0] = -1), tokens [B][N] (tokens[0] =
+ *   root_token[b]), p_draft [B][N] float = softmax(row/T)[token] (entry 0 = 0), level [B][N]
+ *   (nullable; root 0).  A sequence whose nchild[] does not describe a tree of exactly N nodes
+ *   (sum != N-1, an entry outside [0, kmax], or a parent that was never created) gets status bit 1,
+ *   parent = -1, tokens = (root, -1, ...), p_draft = 0.  A child beyond the V-th has token -1. */
+int oracle_build_tree(int32_t B, int32_t N, int32_t V, int32_t dtype, double temperature,
+                      const void* draft_logits, const int32_t* nchild, const int32_t* root_token,
+                      int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
+                      int32_t* status);
+
 int oracle_num_threads(void);
 
 #ifdef __cplusplus

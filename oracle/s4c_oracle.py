@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -201,3 +201,21 @@ def commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_len, f
                                 C.c_int32(fb), _p(features_out), _p(dst), _p(status))
     assert rc == 0
     return dst, status
+
+
+def build_tree(draft_logits, nchild, root_token, kmax, temperature=1.0):
+    """draft_logits [B][N][V], nchild [B][N] -> dict(parent, tokens, p_draft, level, status)"""
+    lib = _load()
+    B, N, V = draft_logits.shape
+    nchild, root_token = _i32(nchild), _i32(root_token)
+    assert nchild.shape == (B, N) and root_token.shape == (B,)
+    parent = np.empty((B, N), dtype=np.int32)
+    tokens = np.empty((B, N), dtype=np.int32)
+    pd = np.empty((B, N), dtype=np.float32)
+    level = np.empty((B, N), dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_build_tree(C.c_int32(B), C.c_int32(N), C.c_int32(V), C.c_int32(_dt(draft_logits)),
+                               C.c_double(temperature), _p(draft_logits), _p(nchild), _p(root_token), C.c_int32(kmax),
+                               _p(parent), _p(tokens), _p(pd), _p(level), _p(status))
+    assert rc == 0, rc
+    return dict(parent=parent, tokens=tokens, p_draft=pd, level=level, status=status)

@@ -241,6 +241,7 @@ class AcceptInputs:
     uniforms: np.ndarray   # [B][N] float32 in [0,1)
     draft_probs: Optional[np.ndarray] = None   # [B][N][V] float32: row u = draft distribution at node u (full_draft)
     u_resample: Optional[np.ndarray] = None    # [B] float32 in [0,1) for the correction token (full_draft)
+    draft_logits: Optional[np.ndarray] = None  # [B][N][V] float32: the logits behind draft_probs (keep_draft_logits)
 
 
 def _softmax64(x: np.ndarray) -> np.ndarray:
@@ -256,7 +257,7 @@ def draw_u_resample(seed: int, B: int, attempt: int = 0) -> np.ndarray:
 
 
 def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int] = None,
-                       threads: int = 8, full_draft: bool = False) -> AcceptInputs:
+                       threads: int = 8, full_draft: bool = False, keep_draft_logits: bool = False) -> AcceptInputs:
     """full_draft (stochastic mode only): also keep every internal node's whole draft
     distribution and draw the uniforms of the correction token; the other arrays are unchanged."""
     seed = cfg.seed() if seed is None else seed
@@ -269,6 +270,9 @@ def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int
     if full_draft and cfg.mode != "stochastic":
         raise ValueError("full_draft needs a stochastic config")
     draft_probs = np.zeros((B, N, V), dtype=np.float32) if full_draft else None
+    if keep_draft_logits and cfg.mode != "stochastic":
+        raise ValueError("keep_draft_logits needs a stochastic config")
+    draft_logits = np.zeros((B, N, V), dtype=np.float32) if keep_draft_logits else None
 
     def one(b):
         logits[b] = _normal(seed, _C_LOGITS, b, (N, V), 2.0, cfg.dtype)
@@ -301,11 +305,13 @@ def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int
                 p_draft[b, ch[u]] = pd[top].astype(np.float32)
                 if full_draft:
                     draft_probs[b, u] = pd.astype(np.float32)
+                if keep_draft_logits:
+                    draft_logits[b, u] = dl
 
     with ThreadPoolExecutor(max_workers=max(1, min(threads, B))) as ex:
         list(ex.map(one, range(B)))
     return AcceptInputs(logits, tokens, p_draft, uniforms, draft_probs,
-                        draw_u_resample(seed, B) if full_draft else None)
+                        draw_u_resample(seed, B) if full_draft else None, draft_logits)
 
 
 def levels_of(parent_row: np.ndarray) -> np.ndarray:
