@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--resample", action="store_true",
                     help="also time s4c_accept_resample (sequential rule with the correction token; stochastic "
                          "configs only; reported as accept_resample, not part of the step)")
+    ap.add_argument("--build-tree", action="store_true",
+                    help="also time s4c_build_tree on bf16 draft logits of the config's shape (reported as "
+                         "build_tree, not part of the step)")
     ap.add_argument("--layers", type=int, default=0,
                     help="also time a whole-model verify: this many layers of tree attention (each with its own KV "
                          "cache), one acceptance, one s4c_commit_path over all layers + feature rows (reported as "
@@ -206,6 +209,29 @@ def main():
         L = tv.accept_len.cpu().numpy()
         rec["accept_resample"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "dtype": "f64",
                                   "accept_len_mean": float(L.mean()), "accept_len_max": int(L.max())}
+    if args.build_tree:
+        d = copies[0]
+        nchild = torch.zeros(cfg.B, cfg.N, dtype=torch.int32, device="cuda")
+        nchild.scatter_add_(1, d["parent"][:, 1:].long(), torch.ones(cfg.B, cfg.N - 1, dtype=torch.int32, device="cuda"))
+        dl = d["logits"] if d["logits"].dtype == torch.bfloat16 else d["logits"].clone()   # any rows of the right shape
+        ws = B.alloc_workspace(B.s4c_build_tree_workspace_size(cfg.B, cfg.N, cfg.V))
+        o_par, o_tok = torch.empty_like(d["parent"]), torch.empty_like(d["parent"])
+        o_pd = torch.empty(cfg.B, cfg.N, dtype=torch.float32, device="cuda")
+        root = d["tokens"][:, 0].contiguous()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for k in range(args.warmup + args.steps):
+            e = evs[k - args.warmup] if k >= args.warmup else None
+            if e:
+                e[0].record()
+            B.s4c_build_tree(dl, nchild, root, 8, o_par, o_tok, o_pd, ws, cfg.temperature)
+            if e:
+                e[1].record()
+        torch.cuda.synchronize()
+        assert torch.equal(o_par, d["parent"])
+        ms = np.array([a.elapsed_time(b) for a, b in evs])
+        rows = int((nchild > 0).sum())
+        rec["build_tree"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "rows_scanned": rows,
+                             "GBps": rows * cfg.V * dl.element_size() / (float(ms.mean()) * 1e-3) / 1e9}
     if args.layers > 0:
         # every layer gets its own K/V cache and tree K/V (device copies of the same synthetic layer)
         Ly, d = args.layers, copies[0]

@@ -149,6 +149,30 @@ s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_d
                                int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Candidate tree from the drafter's logits (Sec. 3.2: the top-1 continuation is drafted first, the
+ * next most probable tokens are placed beside it as alternatives at the same position).
+ *   draft_logits [B][N][V] (logits_dtype): row i = the drafter's logits for the token that follows
+ *                node i; rows of nodes without children are not read.
+ *   nchild       [B][N]: number of children of node i, 0 .. kmax (kmax <= 8).
+ *   root_token   [B]: the last committed token (node 0).
+ *   Nodes are numbered level by level: the children of node i take the next nchild[i] unused
+ *   numbers, in order of decreasing logit (equal logits: lowest token id first), so
+ *   parent[i] < i and siblings are contiguous -- the layout s4c_tree_attn / s4c_accept_path expect.
+ *   parent  [B][N] (parent[0] = -1)       tokens [B][N] (tokens[0] = root_token[b])
+ *   p_draft [B][N] fp32 = softmax(row / T)[token] of the parent's row (entry 0 = 0)
+ *   level   [B][N] nullable: depth of every node (root 0)
+ *   status  [B] nullable: S4C_SEQ_BAD_TREE if nchild[] does not describe a tree of exactly N nodes
+ *           (sum != N-1, an entry outside [0, kmax], or a node that would be a parent before it was
+ *           handed out); then parent = -1, tokens = (root, -1, ...), p_draft = 0, level = 0.
+ *   A child beyond the V-th token of its row gets token -1 and probability 0.
+ *   workspace >= s4c_build_tree_workspace_size(B, N, V) bytes, 256-byte aligned, uninitialised.
+ * Probabilities are computed in fp32. */
+size_t s4c_build_tree_workspace_size(int32_t B, int32_t N, int32_t V);
+s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
+                          const void* draft_logits, const int32_t* nchild, const int32_t* root_token,
+                          int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
+                          int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* KV reuse (Sec. 3.2, last paragraph): for k = 0 .. accept_len[b], tree row path[b][k] of every
  * KV head is copied to cache row cache_len[b] + k (K and V); then cache_len[b] += accept_len[b]+1.
  * Only shape->B, Hkv, D, N, S_cap, dtype are used.

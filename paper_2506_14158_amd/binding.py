@@ -20,7 +20,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
-           "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path")
+           "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size")
 
 
 class S4CError(RuntimeError):
@@ -67,6 +67,11 @@ def lib() -> C.CDLL:
         L.s4c_commit_path.restype = C.c_int
         L.s4c_commit_path.argtypes = [C.POINTER(AttnShape), C.c_int32] + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p,
                                                                                           C.c_int32] + [C.c_void_p] * 4
+        L.s4c_build_tree_workspace_size.restype = C.c_size_t
+        L.s4c_build_tree_workspace_size.argtypes = [C.c_int32] * 3
+        L.s4c_build_tree.restype = C.c_int
+        L.s4c_build_tree.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 3 + [C.c_int32] + [
+            C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         L.s4c_strerror.restype = C.c_char_p
         L.s4c_strerror.argtypes = [C.c_int]
         _lib = L
@@ -231,6 +236,27 @@ def s4c_commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_le
     _check(lib().s4c_commit_path(C.byref(shape), int(Ly), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
                                  _ptr(cache_len), _ptr(path), _ptr(accept_len), max_path, _ptr(features), fb,
                                  _ptr(features_out), _ptr(dst_index), _ptr(status), _stream()))
+
+
+def s4c_build_tree_workspace_size(B: int, N: int, V: int) -> int:
+    return int(lib().s4c_build_tree_workspace_size(B, N, V))
+
+
+def s4c_build_tree(draft_logits, nchild, root_token, kmax: int, parent, tokens, p_draft, workspace,
+                   temperature: float = 1.0, level: Optional[torch.Tensor] = None,
+                   status: Optional[torch.Tensor] = None) -> None:
+    B, N, V = draft_logits.shape
+    for t in (nchild, parent, tokens) + ((level,) if level is not None else ()):
+        if t.dtype != torch.int32 or tuple(t.shape) != (B, N):
+            raise TypeError("nchild / parent / tokens / level must be int32 [B][N]")
+    if root_token.dtype != torch.int32 or tuple(root_token.shape) != (B,):
+        raise TypeError("root_token must be int32 [B]")
+    if p_draft.dtype != torch.float32 or tuple(p_draft.shape) != (B, N):
+        raise TypeError("p_draft must be float32 [B][N]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().s4c_build_tree(B, N, V, _dtype_code(draft_logits), float(temperature), _ptr(draft_logits),
+                                _ptr(nchild), _ptr(root_token), int(kmax), _ptr(parent), _ptr(tokens), _ptr(p_draft),
+                                _ptr(level), _ptr(status), _ptr(workspace), ws_bytes, _stream()))
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:

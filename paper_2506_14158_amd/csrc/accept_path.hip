@@ -8,47 +8,13 @@
 // Kernel 2 (path): one workgroup per sequence combines the chunk statistics per row, applies
 // the per-node test against the parent's row, ANDs along each node's ancestor chain and picks
 // the deepest accepted node (lowest index among equals), writing the path root..node.
-#include "common.h"
+#include "row_chunk.h"
 
 namespace s4c {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kPerThread = 32;                       // logits per thread
-constexpr int kChunk = kThreads * kPerThread;        // logits per workgroup
-
-struct MaxIdx {
-    float v;
-    int32_t i;
-};
-
-__device__ __forceinline__ MaxIdx better(MaxIdx a, MaxIdx b) {
-    // larger value wins; equal values: lower index wins (never depends on reduction order)
-    const bool take_b = (b.v > a.v) || (b.v == a.v && b.i < a.i);
-    return take_b ? b : a;
-}
-
-__device__ __forceinline__ MaxIdx wave_best(MaxIdx x) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        MaxIdx y;
-        y.v = __shfl_xor(x.v, off);
-        y.i = __shfl_xor(x.i, off);
-        x = better(x, y);
-    }
-    return x;
-}
-
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-    return x;
-}
-
-template <typename T> struct Vec16;   // 16-byte vector of T
-template <> struct Vec16<float> { static constexpr int n = 4; };
-template <> struct Vec16<bf16_t> { static constexpr int n = 8; };
+using namespace rowchunk;
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
@@ -62,49 +28,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
 
     float x[kPerThread];
     int32_t idx0[NV];                                  // index of the first element of each vector
-    const bool vec_ok = ((((uintptr_t)base) & 15) == 0);
-    if (vec_ok) {
-#pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int e0 = c0 + (j * kThreads + tid) * VN;
-            idx0[j] = e0;
-            if (e0 + VN <= cend) {
-                const uint4 raw = *(const uint4*)(base + e0);
-                if constexpr (VN == 4) {
-                    x[j * VN + 0] = __uint_as_float(raw.x);
-                    x[j * VN + 1] = __uint_as_float(raw.y);
-                    x[j * VN + 2] = __uint_as_float(raw.z);
-                    x[j * VN + 3] = __uint_as_float(raw.w);
-                } else {
-                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        x[j * VN + 2 * k] = __uint_as_float(w[k] << 16);
-                        x[j * VN + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < VN; ++k) x[j * VN + k] = (e0 + k < cend) ? to_f32<T>(base[e0 + k]) : -INFINITY;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int e0 = c0 + (j * kThreads + tid) * VN;
-            idx0[j] = e0;
-#pragma unroll
-            for (int k = 0; k < VN; ++k) x[j * VN + k] = (e0 + k < cend) ? to_f32<T>(base[e0 + k]) : -INFINITY;
-        }
-    }
-
-    // per-thread argmax in ascending index order: strict '>' keeps the lowest index
-    MaxIdx best = {-INFINITY, 0x7FFFFFFF};
-#pragma unroll
-    for (int j = 0; j < NV; ++j)
-#pragma unroll
-        for (int k = 0; k < VN; ++k)
-            if (x[j * VN + k] > best.v) { best.v = x[j * VN + k]; best.i = idx0[j] + k; }
+    load_chunk<T>(base, c0, cend, tid, x, idx0);
+    MaxIdx best = thread_best<VN>(x, idx0);
     best = wave_best(best);
 
     __shared__ float s_v[4];

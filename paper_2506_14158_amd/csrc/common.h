@@ -120,6 +120,28 @@ struct CompactArgs {
 };
 hipError_t launch_compact(const CompactArgs& a, hipStream_t st);
 
+struct BuildArgs {
+    const void* logits;        // draft logits [B][N][V]
+    const int32_t* nchild;     // [B][N]
+    const int32_t* root_token; // [B]
+    int32_t* parent;
+    int32_t* tokens;
+    float* p_draft;
+    int32_t* level;            // nullable
+    int32_t* status;           // nullable
+    float* ws_max;             // [B*N][chunks]
+    float* ws_sum;             // [B*N][chunks]
+    float* ws_topv;            // [B*N][chunks][8]
+    int32_t* ws_topi;          // [B*N][chunks][8]
+    int32_t* row_tok;          // [B*N][8]
+    float* row_p;              // [B*N][8]
+    int32_t B, N, V, chunks, kmax, dtype;
+    float inv_temp_log2;
+};
+hipError_t launch_build_tree(const BuildArgs& a, hipStream_t st);
+int build_tree_max_children();
+int build_tree_chunk_elems();
+
 struct CommitArgs {
     const void* k_tree;        // [layers][B][N][Hkv][D]
     const void* v_tree;

@@ -225,6 +225,51 @@ s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const
     return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+namespace {
+struct BuildLayout { size_t chunks, off_sum, off_topv, off_topi, off_tok, off_p, total; };
+BuildLayout build_layout(int32_t B, int32_t N, int32_t V) {
+    BuildLayout l;
+    l.chunks = ((size_t)V + build_tree_chunk_elems() - 1) / build_tree_chunk_elems();
+    const size_t rows = (size_t)B * N, K = (size_t)build_tree_max_children();
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    size_t o = 0;
+    o += up(rows * l.chunks * 4); l.off_sum = o;
+    o += up(rows * l.chunks * 4); l.off_topv = o;
+    o += up(rows * l.chunks * K * 4); l.off_topi = o;
+    o += up(rows * l.chunks * K * 4); l.off_tok = o;
+    o += up(rows * K * 4); l.off_p = o;
+    o += up(rows * K * 4); l.total = o;
+    return l;
+}
+}  // namespace
+
+size_t s4c_build_tree_workspace_size(int32_t B, int32_t N, int32_t V) {
+    if (B <= 0 || N <= 0 || V <= 0) return 0;
+    return build_layout(B, N, V).total;
+}
+
+s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
+                          const void* draft_logits, const int32_t* nchild, const int32_t* root_token,
+                          int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
+                          int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!draft_logits || !nchild || !root_token || !parent || !tokens || !p_draft) return S4C_ERR_NULL;
+    if (B <= 0 || N <= 0 || V <= 0 || kmax <= 0 || !(temperature > 0.f)) return S4C_ERR_SHAPE;
+    if (N > kMaxNodes || kmax > build_tree_max_children() || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16))
+        return S4C_ERR_UNSUPPORTED;
+    const BuildLayout l = build_layout(B, N, V);
+    if ((size_t)B * N * l.chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < l.total || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
+    BuildArgs a;
+    a.logits = draft_logits; a.nchild = nchild; a.root_token = root_token; a.parent = parent; a.tokens = tokens;
+    a.p_draft = p_draft; a.level = level; a.status = status;
+    char* w = (char*)workspace;
+    a.ws_max = (float*)w; a.ws_sum = (float*)(w + l.off_sum); a.ws_topv = (float*)(w + l.off_topv);
+    a.ws_topi = (int32_t*)(w + l.off_topi); a.row_tok = (int32_t*)(w + l.off_tok); a.row_p = (float*)(w + l.off_p);
+    a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)l.chunks; a.kmax = kmax; a.dtype = logits_dtype;
+    a.inv_temp_log2 = kLog2e / temperature;
+    return launch_build_tree(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
 s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
                            void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
                            const int32_t* accept_len, int32_t max_path, const void* features,

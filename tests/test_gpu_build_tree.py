@@ -1,0 +1,115 @@
+"""GPU-vs-oracle parity of s4c_build_tree (candidate tree from draft logits and child counts):
+parent, tokens and levels bit-exact; draft probabilities fp32 against the oracle's double
+(relative 1e-5, the fp32 bar)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import s4c_oracle as O
+from paper_2506_14158_amd import binding as B, synth
+from paper_2506_14158_amd.device import np_to_torch
+
+pytestmark = pytest.mark.gpu
+C = synth.CONFIGS
+
+
+def run(draft_logits, nchild, root, kmax, T=1.0):
+    Bn, N, V = draft_logits.shape
+    dl = np_to_torch(draft_logits)
+    i32 = lambda *s: torch.full(s, -7, dtype=torch.int32, device="cuda")
+    parent, tokens, level, status = i32(Bn, N), i32(Bn, N), i32(Bn, N), i32(Bn)
+    pd = torch.full((Bn, N), -7.0, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(B.s4c_build_tree_workspace_size(Bn, N, V))
+    ws.fill_(0xAB)                                        # the workspace need not be initialised
+    B.s4c_build_tree(dl, torch.from_numpy(nchild).cuda(), torch.from_numpy(root.astype(np.int32)).cuda(), kmax, parent,
+                     tokens, pd, ws, T, level, status)
+    torch.cuda.synchronize()
+    return dict(parent=parent.cpu().numpy(), tokens=tokens.cpu().numpy(), p_draft=pd.cpu().numpy(),
+                level=level.cpu().numpy(), status=status.cpu().numpy())
+
+
+def same(g, r):
+    for k in ("status", "parent", "tokens", "level"):
+        assert np.array_equal(g[k], r[k]), k
+    np.testing.assert_allclose(g["p_draft"], r["p_draft"], rtol=1e-5, atol=1e-30)
+
+
+def counts_of(par):
+    nchild = np.zeros_like(par)
+    for b in range(par.shape[0]):
+        for i in range(1, par.shape[1]):
+            nchild[b, par[b, i]] += 1
+    return nchild
+
+
+@pytest.mark.parametrize("cfg", [synth.scaled(C[3], name="13b-small", B=3, V=9000, index=0),
+                                 synth.scaled(C[3], name="13b-v-odd", B=2, V=8191 * 3 + 5, index=0),
+                                 synth.scaled(C[5], name="70b-small", B=2, V=20000, index=0),
+                                 synth.scaled(C[3], name="13b-temp", B=2, V=5000, temperature=0.7, index=0),
+                                 C[3]], ids=lambda c: c.name)
+def test_rebuilds_the_synthetic_trees(cfg):
+    """fp32 draft logits of the seeded workload: the GPU must reproduce the generator's tree and the oracle."""
+    par = synth.make_parent(cfg)
+    ac = synth.make_accept_inputs(cfg, par, keep_draft_logits=True, threads=16)
+    nchild = counts_of(par)
+    kmax = int(nchild.max())
+    g = run(ac.draft_logits, nchild, ac.tokens[:, 0], kmax, cfg.temperature)
+    r = O.build_tree(ac.draft_logits, nchild, ac.tokens[:, 0], kmax, cfg.temperature)
+    same(g, r)
+    assert np.array_equal(g["parent"], par) and np.array_equal(g["tokens"], ac.tokens)
+    if cfg.temperature == 1.0:
+        np.testing.assert_allclose(g["p_draft"], ac.p_draft, rtol=1e-5)
+
+
+def test_full_size_bf16_rows_with_ties():
+    """Config 5's shape with bf16 draft logits (equal values are common: lowest token id first)."""
+    cfg = C[5]
+    par = synth.make_parent(cfg)
+    rng = np.random.default_rng(9)
+    dl = synth.f32_to_bf16_bits((2 * rng.standard_normal((cfg.B, cfg.N, cfg.V), dtype=np.float32)))
+    nchild = counts_of(par)
+    g = run(dl, nchild, np.arange(cfg.B), 8)
+    r = O.build_tree(dl, nchild, np.arange(cfg.B), 8)
+    same(g, r)
+    assert np.array_equal(g["parent"], par)
+
+
+def test_massive_ties_small_vocabulary_and_bad_counts():
+    rng = np.random.default_rng(2)
+    # integer-valued logits: dozens of equal maxima per row, selection must go by token id
+    Bn, N, V = 2, 10, 20000
+    dl = synth.f32_to_bf16_bits(np.round(rng.standard_normal((Bn, N, V)).astype(np.float32)))
+    nchild = np.array([[8, 1, 0, 0, 0, 0, 0, 0, 0, 0], [3, 3, 3, 0, 0, 0, 0, 0, 0, 0]], dtype=np.int32)
+    same(run(dl, nchild, np.array([1, 2]), 8), O.build_tree(dl, nchild, np.array([1, 2]), 8))
+    # fewer tokens than children; invalid child counts
+    lg = np.zeros((4, 4, 2), np.float32)
+    lg[:, :, 1] = 1.0
+    nchild = np.array([[3, 0, 0, 0], [1, 0, 1, 0], [2, 2, 0, 0], [4, 0, 0, 0]], dtype=np.int32)
+    g = run(lg, nchild, np.array([5, 5, 5, 5]), 3)
+    same(g, O.build_tree(lg, nchild, np.array([5, 5, 5, 5]), 3))
+    assert g["status"].tolist() == [0, 1, 1, 1] and g["tokens"][0].tolist() == [5, 1, 0, -1]
+    # a single node
+    one = np.ascontiguousarray(lg[:, :1])
+    same(run(one, np.zeros((4, 1), np.int32), np.arange(4), 1), O.build_tree(one, np.zeros((4, 1), np.int32), np.arange(4), 1))
+
+
+def test_built_tree_feeds_the_verification_step():
+    """End to end on the device: build the tree, then attention + acceptance on the built arrays
+    give what they give on the generator's arrays."""
+    cfg = synth.scaled(C[3], name="e2e", B=2, Hq=4, Hkv=4, P=200, V=6000, index=0)
+    par = synth.make_parent(cfg)
+    ac = synth.make_accept_inputs(cfg, par, keep_draft_logits=True)
+    g = run(ac.draft_logits, counts_of(par), ac.tokens[:, 0], 8)
+    r = O.accept_path(ac.logits, g["parent"], g["tokens"], "stochastic", cfg.levels, g["p_draft"], ac.uniforms, 1.0)
+    r0 = O.accept_path(ac.logits, par, ac.tokens, "stochastic", cfg.levels, ac.p_draft, ac.uniforms, 1.0)
+    assert np.array_equal(r["path"], r0["path"])
+
+
+def test_rejects_bad_arguments():
+    t = torch.zeros(1, 2, 8, device="cuda")
+    i = lambda *s: torch.zeros(*s, dtype=torch.int32, device="cuda")
+    ws = B.alloc_workspace(B.s4c_build_tree_workspace_size(1, 2, 8))
+    with pytest.raises(B.S4CError):      # more children per node than the kernels handle
+        B.s4c_build_tree(t, i(1, 2), i(1), 9, i(1, 2), i(1, 2), torch.zeros(1, 2, device="cuda"), ws)
+    with pytest.raises(B.S4CError):      # workspace too small
+        B.s4c_build_tree(t, i(1, 2), i(1), 2, i(1, 2), i(1, 2), torch.zeros(1, 2, device="cuda"), ws[:16])
