@@ -201,6 +201,21 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
                            int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
                            void* hip_stream);
 
+/* Measurement probes: no part of the verification step.  They give the benchmark the streaming-read
+ * rate and the dense bf16 matrix-core rate that plain kernels reach on the GPU at hand, next to
+ * the published peaks the rooflines are priced against.  The caller times them with events.
+ *   s4c_probe_stream_read  reads `bytes` (>= 16, buffer 16-byte aligned, device) once with 16-byte
+ *                          loads from 4096 workgroups; sink: one device float (left alone).
+ *   s4c_probe_mfma_bf16    256 workgroups x 8 wavefronts x iters x 32 v_mfma_f32_32x32x16_bf16 on
+ *                          register operands that are one constant (random_operands = 0) or drawn
+ *                          from an approximate standard normal (1) -- the rate depends on the data,
+ *                          because the clock follows the multipliers' switching power.
+ *                          sink: >= s4c_probe_mfma_sink_bytes() device bytes (overwritten);
+ *                          *flops (host, nullable) receives the FLOP count of the launch. */
+s4c_status s4c_probe_stream_read(const void* buffer, size_t bytes, float* sink, void* hip_stream);
+size_t s4c_probe_mfma_sink_bytes(void);
+s4c_status s4c_probe_mfma_bf16(int32_t random_operands, int32_t iters, float* sink, double* flops, void* hip_stream);
+
 /* Static, never NULL. */
 const char* s4c_strerror(s4c_status code);
 

@@ -20,7 +20,8 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
-           "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size")
+           "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
+           "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
 
 
 class S4CError(RuntimeError):
@@ -72,6 +73,12 @@ def lib() -> C.CDLL:
         L.s4c_build_tree.restype = C.c_int
         L.s4c_build_tree.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 3 + [C.c_int32] + [
             C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_probe_stream_read.restype = C.c_int
+        L.s4c_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.s4c_probe_mfma_sink_bytes.restype = C.c_size_t
+        L.s4c_probe_mfma_sink_bytes.argtypes = []
+        L.s4c_probe_mfma_bf16.restype = C.c_int
+        L.s4c_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         L.s4c_strerror.restype = C.c_char_p
         L.s4c_strerror.argtypes = [C.c_int]
         _lib = L
@@ -257,6 +264,20 @@ def s4c_build_tree(draft_logits, nchild, root_token, kmax: int, parent, tokens, 
     _check(lib().s4c_build_tree(B, N, V, _dtype_code(draft_logits), float(temperature), _ptr(draft_logits),
                                 _ptr(nchild), _ptr(root_token), int(kmax), _ptr(parent), _ptr(tokens), _ptr(p_draft),
                                 _ptr(level), _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+
+
+def s4c_probe_stream_read(buffer: torch.Tensor, sink: torch.Tensor) -> None:
+    """Enqueue one streaming read of `buffer` (measurement probe; time it with events)."""
+    _check(lib().s4c_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink), _stream()))
+
+
+def s4c_probe_mfma_bf16(random_operands: bool, iters: int, sink: torch.Tensor) -> float:
+    """Enqueue the matrix-core probe; returns the FLOP count of the launch."""
+    if sink.numel() * sink.element_size() < lib().s4c_probe_mfma_sink_bytes():
+        raise ValueError("sink too small")
+    flops = C.c_double(0.0)
+    _check(lib().s4c_probe_mfma_bf16(int(bool(random_operands)), int(iters), _ptr(sink), C.byref(flops), _stream()))
+    return float(flops.value)
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:

@@ -161,4 +161,10 @@ struct CommitArgs {
 };
 hipError_t launch_commit(const CommitArgs& a, hipStream_t st);
 
+// measurement probes (probes.hip)
+hipError_t launch_probe_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
+hipError_t launch_probe_mfma(int random_operands, int iters, float* sink, hipStream_t st);
+double probe_mfma_flops(int iters);
+size_t probe_mfma_sink_floats();
+
 }  // namespace s4c

@@ -301,5 +301,20 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
     return launch_commit(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+s4c_status s4c_probe_stream_read(const void* buffer, size_t bytes, float* sink, void* hip_stream) {
+    if (!buffer || !sink) return S4C_ERR_NULL;
+    if (bytes < 16 || (((uintptr_t)buffer) & 15)) return S4C_ERR_SHAPE;
+    return launch_probe_stream_read(buffer, bytes, sink, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
+size_t s4c_probe_mfma_sink_bytes(void) { return probe_mfma_sink_floats() * sizeof(float); }
+
+s4c_status s4c_probe_mfma_bf16(int32_t random_operands, int32_t iters, float* sink, double* flops, void* hip_stream) {
+    if (!sink) return S4C_ERR_NULL;
+    if (iters <= 0) return S4C_ERR_SHAPE;
+    if (flops) *flops = probe_mfma_flops(iters);
+    return launch_probe_mfma(random_operands ? 1 : 0, iters, sink, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -21,7 +21,7 @@ def L():
 
 def test_every_declared_symbol_is_exported(L):
     hdr = open(os.path.join(ROOT, "include", "s4c.h")).read()
-    declared = set(re.findall(r"\b(s4c_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(s4c_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
