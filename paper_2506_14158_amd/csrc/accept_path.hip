@@ -1,10 +1,12 @@
 // Path acceptance (paper Sec. 3.2: per-node test, then the longest accepted path).
 //
-// Kernel 1 (row_stats): the HBM-bound part.  Each workgroup reads one chunk of one logits row
-// exactly once with 16-byte loads, keeps the values in registers, and reduces
+// Kernel 1 (row_stats): the HBM-bound part.  Each workgroup reads a segment of consecutive
+// 8192-logit chunks of one logits row exactly once with 16-byte loads (the next chunk in flight
+// while the current one is reduced in registers), and reduces
 //   (max value, lowest index attaining it)   -- argmax, ties to the lowest token id
-//   sum exp2((x - chunk max) * log2(e)/T)    -- stochastic mode only
-// with wavefront shuffles, then across the 4 waves through LDS.
+//   sum exp2((x - segment max) * log2(e)/T)  -- stochastic mode only
+// per thread first (no barrier inside the segment), then with wavefront shuffles and across the
+// 4 waves through LDS.
 // Kernel 2 (path): one workgroup per sequence combines the chunk statistics per row, applies
 // the per-node test against the parent's row, ANDs along each node's ancestor chain and picks
 // the deepest accepted node (lowest index among equals), writing the path root..node.
@@ -19,40 +21,89 @@ using namespace rowchunk;
 template <typename T>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
     constexpr int VN = Vec16<T>::n;
-    constexpr int NV = kPerThread / VN;               // 16-byte loads per thread
-    const int row = blockIdx.x / a.chunks, ch = blockIdx.x % a.chunks, tid = threadIdx.x;
+    constexpr int NV = kPerThread / VN;               // 16-byte loads per thread and chunk
+    const int row = blockIdx.x / a.nseg, sg = blockIdx.x % a.nseg, tid = threadIdx.x;
     const int V = a.V;
     const T* base = (const T*)a.logits + (size_t)row * V;
-    const int c0 = ch * kChunk;
-    const int cend = min(V, c0 + kChunk);
+    const int ch0 = sg * a.seg, ch1 = min(a.chunks, ch0 + a.seg);
+    const bool vec_ok = ((((uintptr_t)base) & 15) == 0);
+    const bool stochastic = a.mode == S4C_STOCHASTIC;
 
-    float x[kPerThread];
-    int32_t idx0[NV];                                  // index of the first element of each vector
-    load_chunk<T>(base, c0, cend, tid, x, idx0);
-    MaxIdx best = thread_best<VN>(x, idx0);
-    best = wave_best(best);
+    // per-thread running state over the segment's chunks: argmax (lowest index among equals: the
+    // scan ascends and '>' is strict), and a sum of exponentials relative to the thread's own
+    // running maximum, rescaled when that grows
+    MaxIdx best = {-INFINITY, 0x7FFFFFFF};
+    float m_t = -INFINITY, s_t = 0.f;
 
+    // whole, aligned chunks are fetched one chunk ahead as raw 16-byte words
+    uint4 raw[NV];
+    auto whole = [&](int ch) { return vec_ok && (ch + 1) * kChunk <= V; };
+    auto fetch = [&](int ch) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) raw[j] = *(const uint4*)(base + ch * kChunk + (j * kThreads + tid) * VN);
+    };
+    bool have = ch0 < ch1 && whole(ch0);
+    if (have) fetch(ch0);
+    for (int ch = ch0; ch < ch1; ++ch) {
+        float x[kPerThread];
+        int32_t idx0[NV];
+        if (have) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                idx0[j] = ch * kChunk + (j * kThreads + tid) * VN;
+                if constexpr (VN == 4) {
+                    x[j * VN + 0] = __uint_as_float(raw[j].x);
+                    x[j * VN + 1] = __uint_as_float(raw[j].y);
+                    x[j * VN + 2] = __uint_as_float(raw[j].z);
+                    x[j * VN + 3] = __uint_as_float(raw[j].w);
+                } else {
+                    const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        x[j * VN + 2 * k] = __uint_as_float(w[k] << 16);
+                        x[j * VN + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+                    }
+                }
+            }
+        } else {
+            load_chunk<T>(base, ch * kChunk, min(V, (ch + 1) * kChunk), tid, x, idx0);
+        }
+        have = ch + 1 < ch1 && whole(ch + 1);
+        if (have) fetch(ch + 1);                       // in flight while this chunk is reduced
+
+        const MaxIdx cb = thread_best<VN>(x, idx0);
+        if (cb.v > best.v) best = cb;
+        if (stochastic && cb.v > -INFINITY) {
+            const float m_new = fmaxf(m_t, cb.v);
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < kPerThread; ++e) sum += fast_exp2((x[e] - m_new) * a.inv_temp_log2);   // padding: 0
+            s_t = s_t * fast_exp2((m_t - m_new) * a.inv_temp_log2) + sum;                                // first chunk: 0 * 0
+            m_t = m_new;
+        }
+    }
+
+    // ---- combine the 256 threads
     __shared__ float s_v[4];
     __shared__ int32_t s_i[4];
     __shared__ float s_s[4];
     const int wave = tid >> 6, lane = tid & 63;
-    if (lane == 0) { s_v[wave] = best.v; s_i[wave] = best.i; }
+    const MaxIdx wb = wave_best(best);
+    if (lane == 0) { s_v[wave] = wb.v; s_i[wave] = wb.i; }
     __syncthreads();
     MaxIdx blk = {s_v[0], s_i[0]};
 #pragma unroll
     for (int w = 1; w < 4; ++w) blk = better(blk, MaxIdx{s_v[w], s_i[w]});
-
     float sum = 0.f;
-    if (a.mode == S4C_STOCHASTIC) {
-#pragma unroll
-        for (int e = 0; e < kPerThread; ++e) sum += fast_exp2((x[e] - blk.v) * a.inv_temp_log2);   // padding: exp2(-inf) = 0
+    if (stochastic) {
+        sum = (m_t > -INFINITY) ? s_t * fast_exp2((m_t - blk.v) * a.inv_temp_log2) : 0.f;
         sum = wave_sum(sum);
         if (lane == 0) s_s[wave] = sum;
         __syncthreads();
         sum = (s_s[0] + s_s[1]) + (s_s[2] + s_s[3]);
     }
     if (tid == 0) {
-        const size_t o = (size_t)row * a.chunks + ch;
+        const size_t o = (size_t)row * a.nseg + sg;
         a.ws_max[o] = blk.v;
         a.ws_arg[o] = blk.i;
         a.ws_sum[o] = sum;
@@ -82,13 +133,13 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
     float m = -INFINITY, S = 0.f;
     int32_t g = 0x7FFFFFFF;
     if (i < N) {
-        const size_t o = ((size_t)b * N + i) * a.chunks;
-        for (int c = 0; c < a.chunks; ++c) {
+        const size_t o = ((size_t)b * N + i) * a.nseg;
+        for (int c = 0; c < a.nseg; ++c) {
             const float v = a.ws_max[o + c];
-            if (v > m) { m = v; g = a.ws_arg[o + c]; }           // chunks ascend: strict '>' keeps lowest index
+            if (v > m) { m = v; g = a.ws_arg[o + c]; }           // segments ascend: strict '>' keeps lowest index
         }
         if (a.mode == S4C_STOCHASTIC)
-            for (int c = 0; c < a.chunks; ++c)
+            for (int c = 0; c < a.nseg; ++c)
                 S += a.ws_sum[o + c] * fast_exp2((a.ws_max[o + c] - m) * a.inv_temp_log2);
         s_g[i] = g;
     }
@@ -159,7 +210,7 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
 int accept_chunk_elems() { return kChunk; }
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
-    dim3 grid((unsigned)(a.chunks * a.B * a.N)), block(kThreads);
+    dim3 grid((unsigned)(a.nseg * a.B * a.N)), block(kThreads);
     if (a.dtype == S4C_F32) hipLaunchKernelGGL(row_stats_kernel<float>, grid, block, 0, st, a);
     else hipLaunchKernelGGL(row_stats_kernel<bf16_t>, grid, block, 0, st, a);
     hipError_t e = hipGetLastError();

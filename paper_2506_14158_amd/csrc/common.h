@@ -72,10 +72,11 @@ struct AcceptArgs {
     int32_t* accepted_tokens;
     int32_t* bonus_token;
     int32_t* status;
-    float* ws_max;     // [B*N][chunks]
-    int32_t* ws_arg;   // [B*N][chunks]
-    float* ws_sum;     // [B*N][chunks]
+    float* ws_max;     // [B*N][nseg]
+    int32_t* ws_arg;   // [B*N][nseg]
+    float* ws_sum;     // [B*N][nseg]
     int32_t B, N, V, chunks, max_path, mode, dtype;
+    int32_t seg, nseg; // chunks per workgroup, workgroups per row
     float inv_temp_log2;   // log2(e) / T
 };
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);

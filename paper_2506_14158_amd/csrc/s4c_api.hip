@@ -170,6 +170,15 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     a.ws_arg = (int32_t*)((char*)workspace + per);
     a.ws_sum = (float*)((char*)workspace + 2 * per);
     a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)chunks;
+    // Segment length: up to about 8192 workgroups per launch, but at least two chunks per workgroup
+    // (so the second streams in while the first is reduced) once there are 4096 chunks to hand out.
+    const size_t units = (size_t)B * N * chunks;
+    size_t seg = (units + 8191) / 8192;
+    if (seg < 2 && units >= 4096) seg = 2;
+    if (seg < 1) seg = 1;
+    if (seg > chunks) seg = chunks;
+    a.seg = (int32_t)seg;
+    a.nseg = (int32_t)((chunks + seg - 1) / seg);
     a.max_path = max_path; a.mode = mode; a.dtype = logits_dtype;
     a.inv_temp_log2 = kLog2e / (mode == S4C_STOCHASTIC ? temperature : 1.0f);
     return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
