@@ -499,3 +499,21 @@ int oracle_build_tree(int32_t B, int32_t N, int32_t V, int32_t dtype, double tem
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ draft-head input projection */
+
+int oracle_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
+                        const void* W, const void* bias, double* out) {
+    if (T < 0 || H < 1 || Hout < 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t o = 0; o < Hout; ++o) {
+            double acc = bias ? load_elem(bias, dtype, (size_t)o) : 0.0;
+            const size_t w0 = (size_t)o * 2 * H;
+            for (int32_t k = 0; k < H; ++k) acc += load_elem(e, dtype, (size_t)t * H + k) * load_elem(W, dtype, w0 + k);
+            for (int32_t k = 0; k < H; ++k) acc += load_elem(f, dtype, (size_t)t * H + k) * load_elem(W, dtype, w0 + H + k);
+            out[(size_t)t * Hout + o] = acc;
+        }
+    return 0;
+}
+

@@ -135,6 +135,12 @@ int oracle_build_tree(int32_t B, int32_t N, int32_t V, int32_t dtype, double tem
                       int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
                       int32_t* status);
 
+/* Input projection of a draft head (Eq. 3: h = Linear(concat[e, f])): out[t][o] = bias[o] +
+ * sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k], in double.  e, f [T][H]; W [Hout][2H] (one row
+ * per output feature, the layout of a linear layer's weight); bias [Hout] nullable; out [T][Hout]. */
+int oracle_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
+                        const void* W, const void* bias, double* out);
+
 int oracle_num_threads(void);
 
 #ifdef __cplusplus

@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -219,3 +219,17 @@ def build_tree(draft_logits, nchild, root_token, kmax, temperature=1.0):
                                _p(parent), _p(tokens), _p(pd), _p(level), _p(status))
     assert rc == 0, rc
     return dict(parent=parent, tokens=tokens, p_draft=pd, level=level, status=status)
+
+
+def draft_linear(e, f, W, bias=None):
+    """e, f [T][H], W [Hout][2H], bias [Hout] or None -> out float64 [T][Hout]"""
+    lib = _load()
+    T, H = e.shape
+    Hout = W.shape[0]
+    assert f.shape == (T, H) and W.shape == (Hout, 2 * H) and _dt(e) == _dt(f) == _dt(W)
+    assert bias is None or (bias.shape == (Hout,) and _dt(bias) == _dt(e))
+    out = np.empty((T, Hout), dtype=np.float64)
+    rc = lib.oracle_draft_linear(C.c_int32(T), C.c_int32(H), C.c_int32(Hout), C.c_int32(_dt(e)), _p(e), _p(f), _p(W),
+                                 _p(bias), _p(out))
+    assert rc == 0
+    return out
