@@ -67,6 +67,18 @@ def cpu_baseline(cfg, par, at, ac, budget_s=15.0):
                       "oracle on %d of %d sequences scaled; est. %.1f s per full step" % (n, total_rows, total_rows / n, nb, cfg.B, t_step)}
 
 
+def _timed_ms(torch, fn, reps=10):
+    """Mean time of `reps` back-to-back calls, by events on the current stream."""
+    fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +90,9 @@ def main():
     ap.add_argument("--resample", action="store_true",
                     help="also time s4c_accept_resample (sequential rule with the correction token; stochastic "
                          "configs only; reported as accept_resample, not part of the step)")
+    ap.add_argument("--draft-linear", action="store_true",
+                    help="also time s4c_draft_linear (Eq. 3) on the config's B*N tokens with hidden size Hq*D "
+                         "(bf16 configs; reported as draft_linear, not part of the step)")
     ap.add_argument("--build-tree", action="store_true",
                     help="also time s4c_build_tree on bf16 draft logits of the config's shape (reported as "
                          "build_tree, not part of the step)")
@@ -234,6 +249,21 @@ def main():
         L = tv.accept_len.cpu().numpy()
         rec["accept_resample"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "dtype": "f64",
                                   "accept_len_mean": float(L.mean()), "accept_len_max": int(L.max())}
+    if args.draft_linear and cfg.dtype == "bf16":
+        Tn, Hd = cfg.B * cfg.N, cfg.Hq * cfg.D
+        g = torch.Generator(device="cuda").manual_seed(1)
+        rn = lambda *s_: torch.randn(*s_, device="cuda", generator=g)
+        e_, f_ = rn(Tn, Hd).bfloat16(), rn(Tn, Hd).bfloat16()
+        W_ = (rn(Hd, 2 * Hd) / (2 * Hd) ** 0.5).bfloat16()
+        b_ = rn(Hd).bfloat16()
+        o_ = torch.empty(Tn, Hd, dtype=torch.bfloat16, device="cuda")
+        t_dl, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: B.s4c_draft_linear(e_, f_, W_, o_, b_)))
+        t_lib, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: torch.addmm(b_, torch.cat([e_, f_], 1), W_.t())))
+        fl = 2.0 * Tn * 2 * Hd * Hd
+        rec["draft_linear"] = {"tokens": Tn, "hidden": Hd, "ms": t_dl, "TFLOPs": fl / t_dl / 1e9,
+                               "frac_of_mfma_peak": fl / t_dl / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                               "torch_cat_addmm_ms": t_lib, "torch_TFLOPs": fl / t_lib / 1e9}
+        del e_, f_, W_, o_
     if args.build_tree:
         d = copies[0]
         nchild = torch.zeros(cfg.B, cfg.N, dtype=torch.int32, device="cuda")

@@ -201,6 +201,16 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
                            int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
                            void* hip_stream);
 
+/* Input projection of a draft head (Eq. 3: h = Linear(concat[e, f])), the concatenation never formed:
+ *   out[t][o] = bias[o] + sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k]
+ *   e, f [T][H]: embedding and feature of every token; W [Hout][2H] (one row per output feature,
+ *   the layout of a linear layer's weight); bias [Hout] nullable; out [T][Hout].
+ *   dtype must be S4C_BF16 (products and sums in fp32, output rounded to nearest even);
+ *   H a multiple of 32 (<= 16384), Hout a multiple of 256, T*H < 2^30; all pointers 16-byte
+ *   aligned device pointers.  No workspace. */
+s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
+                            const void* W, const void* bias, void* out, void* hip_stream);
+
 /* Measurement probes: no part of the verification step.  They give the benchmark the streaming-read
  * rate and the dense bf16 matrix-core rate that plain kernels reach on the GPU at hand, next to
  * the published peaks the rooflines are priced against.  The caller times them with events.

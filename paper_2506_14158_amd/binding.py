@@ -21,7 +21,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
+           "s4c_draft_linear", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
 
 
 class S4CError(RuntimeError):
@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.s4c_build_tree.restype = C.c_int
         L.s4c_build_tree.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 3 + [C.c_int32] + [
             C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_draft_linear.restype = C.c_int
+        L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6
         L.s4c_probe_stream_read.restype = C.c_int
         L.s4c_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.s4c_probe_mfma_sink_bytes.restype = C.c_size_t
@@ -264,6 +266,21 @@ def s4c_build_tree(draft_logits, nchild, root_token, kmax: int, parent, tokens, 
     _check(lib().s4c_build_tree(B, N, V, _dtype_code(draft_logits), float(temperature), _ptr(draft_logits),
                                 _ptr(nchild), _ptr(root_token), int(kmax), _ptr(parent), _ptr(tokens), _ptr(p_draft),
                                 _ptr(level), _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+
+
+def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
+    """out[t] = W @ concat(e[t], f[t]) + bias (bf16, fp32 accumulate); returns ``out``."""
+    T, H = e.shape
+    Hout = W.shape[0]
+    if tuple(f.shape) != (T, H) or tuple(W.shape) != (Hout, 2 * H) or tuple(out.shape) != (T, Hout):
+        raise ValueError("e, f [T][H]; W [Hout][2H]; out [T][Hout]")
+    if bias is not None and tuple(bias.shape) != (Hout,):
+        raise ValueError("bias [Hout]")
+    for t in (e, f, W, out) + ((bias,) if bias is not None else ()):
+        if t.dtype != torch.bfloat16:
+            raise TypeError("s4c_draft_linear takes bfloat16 tensors")
+    _check(lib().s4c_draft_linear(T, H, Hout, S4C_BF16, _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out), _stream()))
+    return out
 
 
 def s4c_probe_stream_read(buffer: torch.Tensor, sink: torch.Tensor) -> None:

@@ -162,6 +162,19 @@ struct CommitArgs {
 };
 hipError_t launch_commit(const CommitArgs& a, hipStream_t st);
 
+struct LinearArgs {
+    const void* e;       // [T][H] bf16
+    const void* f;       // [T][H] bf16
+    const void* W;       // [Hout][2H] bf16
+    const void* bias;    // [Hout] bf16 or null
+    void* out;           // [T][Hout] bf16
+    int32_t T, H, Hout;
+    int32_t ttiles, otiles;   // set by the launcher
+};
+hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st);
+int draft_linear_tile_out();
+int draft_linear_tile_k();
+
 // measurement probes (probes.hip)
 hipError_t launch_probe_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
 hipError_t launch_probe_mfma(int random_operands, int iters, float* sink, hipStream_t st);

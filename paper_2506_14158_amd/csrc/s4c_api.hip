@@ -310,6 +310,19 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
     return launch_commit(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
+                            const void* W, const void* bias, void* out, void* hip_stream) {
+    if (!e || !f || !W || !out) return S4C_ERR_NULL;
+    if (T <= 0 || H <= 0 || Hout <= 0) return S4C_ERR_SHAPE;
+    if (dtype != S4C_BF16 || H % draft_linear_tile_k() != 0 || Hout % draft_linear_tile_out() != 0 ||
+        (long long)T * H * 2 >= (1ll << 31) || H > 16384)
+        return S4C_ERR_UNSUPPORTED;
+    if ((((uintptr_t)e) | ((uintptr_t)f) | ((uintptr_t)W) | ((uintptr_t)out)) & 15) return S4C_ERR_SHAPE;
+    LinearArgs a;
+    a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.T = T; a.H = H; a.Hout = Hout; a.ttiles = a.otiles = 0;
+    return launch_draft_linear(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
 s4c_status s4c_probe_stream_read(const void* buffer, size_t bytes, float* sink, void* hip_stream) {
     if (!buffer || !sink) return S4C_ERR_NULL;
     if (bytes < 16 || (((uintptr_t)buffer) & 15)) return S4C_ERR_SHAPE;
