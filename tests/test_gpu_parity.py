@@ -69,6 +69,30 @@ def test_tree_attn_elementwise(cfg):
     check_attn_full(cfg)
 
 
+def _random_shapes():
+    """Seeded sweep over shapes that land in each attention kernel (scalar; matrix-core with <= 64,
+    <= 128 and > 128 query rows per KV head), with odd sizes, ragged lengths and forced KV splits."""
+    rng = np.random.default_rng(20250614)
+    shapes = []
+    for k in range(20):
+        dtype = "f32" if k % 5 == 4 else "bf16"
+        D = 64 if (dtype == "f32" or k % 7 == 3) else 128
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        N = int(rng.integers(1, 129)) if k % 3 else int(rng.integers(1, 20))
+        levels = 1 if N == 1 else int(min(N, rng.integers(2, 4) if N <= 9 else rng.integers(4, 9)))
+        P = int(rng.choice([0, 1, 31, 63, 64, 65, 200, 777, 1500, 4100]))
+        shapes.append(synth.scaled(C[4], name="rnd%d-%s-d%d-g%d-n%d-p%d" % (k, dtype, D, G, N, P), B=int(rng.integers(1, 4)),
+                                   Hq=Hkv * G, Hkv=Hkv, D=D, dtype=dtype, P=P, N=N, levels=levels,
+                                   widths=(8, 4, 3, 2, 2, 2, 2, 2), ragged=bool(k % 2) and P > 1, index=0))
+    return shapes
+
+
+@pytest.mark.parametrize("cfg", _random_shapes(), ids=lambda c: c.name)
+def test_tree_attn_random_shapes(cfg):
+    check_attn_full(cfg)
+
+
 def test_tree_attn_custom_scale_and_chain():
     cfg = synth.scaled(C[2], name="chain", Hq=2, Hkv=2, P=100, N=40, levels=40, index=0)
     par = np.arange(-1, cfg.N - 1, dtype=np.int32)[None]
