@@ -46,6 +46,7 @@ def counts_of(par):
                                  synth.scaled(C[3], name="13b-v-odd", B=2, V=8191 * 3 + 5, index=0),
                                  synth.scaled(C[5], name="70b-small", B=2, V=20000, index=0),
                                  synth.scaled(C[3], name="13b-temp", B=2, V=5000, temperature=0.7, index=0),
+                                 synth.scaled(C[3], name="13b-v-1m", B=1, V=1_000_003, N=6, levels=3, index=0),
                                  C[3]], ids=lambda c: c.name)
 def test_rebuilds_the_synthetic_trees(cfg):
     """fp32 draft logits of the seeded workload: the GPU must reproduce the generator's tree and the oracle."""

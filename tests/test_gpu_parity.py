@@ -199,6 +199,8 @@ ACCEPT_SMALL = [
     synth.scaled(C[3], name="13b-temp", B=2, V=9000, temperature=0.7, index=0),
     synth.scaled(C[5], name="70b-small", B=2, V=20000, index=0),
     synth.scaled(C[1], name="f32-stochastic", mode="stochastic", B=4, V=5000, N=31, levels=5, index=0),
+    synth.scaled(C[2], name="7b-v-1m", B=2, V=1_000_003, N=9, levels=3, index=0),           # a million-token row, odd length
+    synth.scaled(C[3], name="13b-v-1m", B=1, V=1_000_003, N=6, levels=3, index=0),
 ]
 
 

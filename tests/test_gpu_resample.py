@@ -52,6 +52,7 @@ SMALL = [
     synth.scaled(C[1], name="f32", mode="stochastic", B=4, V=5000, N=31, levels=5, index=0),
     synth.scaled(C[1], name="f32-v-odd", mode="stochastic", B=2, V=1003, N=15, levels=4, index=0),
     synth.scaled(C[3], name="root-only", B=3, V=4000, N=1, levels=1, index=0),
+    synth.scaled(C[3], name="13b-v-1m", B=2, V=1_000_003, N=6, levels=3, index=0),        # long, odd rows; 16 workgroups each
 ]
 
 
