@@ -129,6 +129,40 @@ def test_tree_attn_flags_bad_sequences_and_zeroes_them():
     assert amax <= 1e-2 and rel <= 2e-2
 
 
+def test_tree_attn_beyond_two_billion_cache_elements():
+    """Config 5's shape with 64 sequences: each of K and V holds 2.16e9 elements (4.3 GB), so every
+    cache offset of the later sequences needs 64-bit arithmetic.  The cache is drawn on the device;
+    the first and the last sequence are copied back and checked against the oracle on sampled rows."""
+    cfg = synth.scaled(C[5], name="b64", B=64, index=0)
+    Bn, N, Hq, Hkv, D, S = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, cfg.S_cap
+    assert Bn * Hkv * S * D > 2 ** 31
+    g = torch.Generator(device="cuda").manual_seed(7)
+    rn = lambda *s_: torch.randn(*s_, device="cuda", generator=g, dtype=torch.float32).bfloat16()
+    kc = torch.empty(Bn, Hkv, S, D, dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(Bn):                                   # per sequence: keeps the fp32 temporaries small
+        kc[b] = rn(Hkv, S, D)
+        vc[b] = rn(Hkv, S, D)
+    q, kt, vt = rn(Bn, N, Hq, D), rn(Bn, N, Hkv, D), rn(Bn, N, Hkv, D)
+    par = synth.make_parent(cfg)
+    cl = torch.full((Bn,), cfg.P, dtype=torch.int32, device="cuda")
+    tv = TreeVerifier(Bn, N, Hq, Hkv, D, S, 8, torch.bfloat16, cfg.levels, cfg.P)
+    tv.tree_attn(q, kt, vt, kc, vc, cl, torch.from_numpy(par).cuda())
+    torch.cuda.synchronize()
+    assert tv.attn_status.cpu().tolist() == [0] * Bn
+    pick = [0, Bn - 1]
+    host = lambda t: np.ascontiguousarray(t[pick].view(torch.int16).cpu().numpy().view(np.uint16))
+    rng = np.random.default_rng(3)
+    n = 48
+    tri = np.stack([rng.integers(0, 2, n), rng.integers(0, N, n), rng.integers(0, Hq, n)], 1).astype(np.int32)
+    tri[0], tri[1] = (1, N - 1, Hq - 1), (0, 0, 0)
+    ref = O.tree_attn_sampled(host(q), host(kt), host(vt), host(kc), host(vc), np.full(2, cfg.P, np.int32),
+                              np.ascontiguousarray(par[pick]), tri)
+    got = tv.out[pick][tri[:, 0], tri[:, 1], tri[:, 2]]
+    amax, rel = attn_errors(got, ref)
+    assert amax <= TOL["bf16"][0] and rel <= TOL["bf16"][1], (amax, rel)
+
+
 def sample_triples(cfg, rng, n):
     t = np.stack([rng.integers(0, cfg.B, n), rng.integers(0, cfg.N, n), rng.integers(0, cfg.Hq, n)], 1).astype(np.int32)
     t[0] = (0, 0, 0)
