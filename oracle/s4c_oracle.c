@@ -517,3 +517,65 @@ int oracle_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const
     return 0;
 }
 
+/* ------------------------------------------------------------------ paged cache */
+
+int oracle_paged_gather(const oracle_shape* s, int32_t page_size, int32_t num_pages, int32_t max_blocks,
+                        const void* pool, const int32_t* block_table, const int32_t* cache_len, void* cache,
+                        int32_t* status) {
+    const size_t row = (size_t)s->D * elem_size(s->dtype);
+    memset(cache, 0, (size_t)s->B * s->Hkv * s->S_cap * row);
+    for (int32_t b = 0; b < s->B; ++b) {
+        const int32_t P = cache_len[b];
+        int bad = (P < 0 || P > s->S_cap || (int64_t)P > (int64_t)max_blocks * page_size);
+        for (int32_t j = 0; !bad && j < P; j += page_size) {
+            const int32_t id = block_table[(size_t)b * max_blocks + j / page_size];
+            if (id < 0 || id >= num_pages) bad = 1;
+        }
+        if (status) status[b] = bad ? ORACLE_BAD_LEN : 0;
+        if (bad) continue;
+        for (int32_t h = 0; h < s->Hkv; ++h)
+            for (int32_t j = 0; j < P; ++j) {
+                const int32_t id = block_table[(size_t)b * max_blocks + j / page_size];
+                const size_t src = (((size_t)id * s->Hkv + h) * page_size + (size_t)(j % page_size)) * row;
+                const size_t dst = (((size_t)b * s->Hkv + h) * s->S_cap + (size_t)j) * row;
+                memcpy((char*)cache + dst, (const char*)pool + src, row);
+            }
+    }
+    return 0;
+}
+
+int oracle_kv_compact_paged(const oracle_shape* s, int32_t page_size, int32_t num_pages, int32_t max_blocks,
+                            const void* k_tree, const void* v_tree, void* k_pool, void* v_pool,
+                            const int32_t* block_table, int32_t* cache_len, const int32_t* path,
+                            const int32_t* accept_len, int32_t max_path, int32_t* dst_index, int32_t* status) {
+    const size_t row = (size_t)s->D * elem_size(s->dtype);
+    for (int32_t b = 0; b < s->B; ++b) {
+        const int32_t L = accept_len[b];
+        const int32_t base = cache_len[b];
+        const int32_t* pth = path + (size_t)b * max_path;
+        if (dst_index)
+            for (int32_t k = 0; k < max_path; ++k) dst_index[(size_t)b * max_path + k] = -1;
+        int bad = (L < 0 || L >= max_path || base < 0 || (int64_t)base + L + 1 > (int64_t)max_blocks * page_size);
+        for (int32_t k = 0; !bad && k <= L; ++k) {
+            if (pth[k] < 0 || pth[k] >= s->N) bad = 1;
+            const int32_t id = block_table[(size_t)b * max_blocks + (base + k) / page_size];
+            if (id < 0 || id >= num_pages) bad = 1;
+        }
+        if (status) status[b] = bad ? ORACLE_BAD_LEN : 0;
+        if (bad) continue;
+        for (int32_t k = 0; k <= L; ++k) {
+            const int32_t j = base + k;
+            const int32_t id = block_table[(size_t)b * max_blocks + j / page_size];
+            for (int32_t h = 0; h < s->Hkv; ++h) {
+                const size_t src = (((size_t)b * s->N + pth[k]) * s->Hkv + h) * row;
+                const size_t dst = (((size_t)id * s->Hkv + h) * page_size + (size_t)(j % page_size)) * row;
+                memcpy((char*)k_pool + dst, (const char*)k_tree + src, row);
+                memcpy((char*)v_pool + dst, (const char*)v_tree + src, row);
+            }
+            if (dst_index) dst_index[(size_t)b * max_path + k] = j;
+        }
+        cache_len[b] = base + L + 1;
+    }
+    return 0;
+}
+

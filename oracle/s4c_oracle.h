@@ -135,6 +135,23 @@ int oracle_build_tree(int32_t B, int32_t N, int32_t V, int32_t dtype, double tem
                       int32_t kmax, int32_t* parent, int32_t* tokens, float* p_draft, int32_t* level,
                       int32_t* status);
 
+/* Paged cache (a serving layout; the paper's Sec. 3.2 reuse step does not fix one).  The pool is
+ * [num_pages][Hkv][page_size][D]; row j of sequence b lives in page block_table[b][j / page_size]
+ * (block_table is [B][max_blocks]) at row j % page_size.  Tree attention over a paged cache is, by
+ * definition, tree attention over the contiguous cache that oracle_paged_gather assembles (rows
+ * j >= cache_len[b] zero); a sequence whose cache_len exceeds S_cap or max_blocks*page_size, or one
+ * of whose needed pages is outside [0, num_pages), gets status bit 2 and an all-zero cache. */
+int oracle_paged_gather(const oracle_shape* s, int32_t page_size, int32_t num_pages, int32_t max_blocks,
+                        const void* pool, const int32_t* block_table, const int32_t* cache_len, void* cache,
+                        int32_t* status);
+
+/* oracle_kv_compact on a paged cache: the accepted rows go to rows cache_len[b] + k of the pages the
+ * block table names (they must already be there); same flagging rule as above for those pages. */
+int oracle_kv_compact_paged(const oracle_shape* s, int32_t page_size, int32_t num_pages, int32_t max_blocks,
+                            const void* k_tree, const void* v_tree, void* k_pool, void* v_pool,
+                            const int32_t* block_table, int32_t* cache_len, const int32_t* path,
+                            const int32_t* accept_len, int32_t max_path, int32_t* dst_index, int32_t* status);
+
 /* Input projection of a draft head (Eq. 3: h = Linear(concat[e, f])): out[t][o] = bias[o] +
  * sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k], in double.  e, f [T][H]; W [Hout][2H] (one row
  * per output feature, the layout of a linear layer's weight); bias [Hout] nullable; out [T][Hout]. */

@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -233,3 +233,38 @@ def draft_linear(e, f, W, bias=None):
                                  _p(bias), _p(out))
     assert rc == 0
     return out
+
+
+def paged_gather(pool, block_table, cache_len, S_cap):
+    """pool [num_pages][Hkv][page_size][D], block_table [B][max_blocks] -> (cache [B][Hkv][S_cap][D], status)"""
+    lib = _load()
+    num_pages, Hkv, page_size, D = pool.shape
+    block_table, cache_len = _i32(block_table), _i32(cache_len)
+    B, max_blocks = block_table.shape
+    s = _Shape(B, Hkv, Hkv, D, 1, S_cap, _dt(pool))
+    cache = np.empty((B, Hkv, S_cap, D), dtype=pool.dtype)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_paged_gather(C.byref(s), C.c_int32(page_size), C.c_int32(num_pages), C.c_int32(max_blocks), _p(pool),
+                                 _p(block_table), _p(cache_len), _p(cache), _p(status))
+    assert rc == 0
+    return cache, status
+
+
+def kv_compact_paged(k_tree, v_tree, k_pool, v_pool, block_table, cache_len, path, accept_len):
+    """In place on k_pool, v_pool, cache_len -> (dst_index, status)"""
+    lib = _load()
+    B, N, Hkv, D = k_tree.shape
+    num_pages, _, page_size, _ = k_pool.shape
+    block_table = _i32(block_table)
+    max_blocks = block_table.shape[1]
+    s = _Shape(B, Hkv, Hkv, D, N, max_blocks * page_size, _dt(k_tree))
+    assert cache_len.dtype == np.int32 and cache_len.flags["C_CONTIGUOUS"]
+    path, accept_len = _i32(path), _i32(accept_len)
+    max_path = path.shape[1]
+    dst = np.empty((B, max_path), dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_kv_compact_paged(C.byref(s), C.c_int32(page_size), C.c_int32(num_pages), C.c_int32(max_blocks),
+                                     _p(k_tree), _p(v_tree), _p(k_pool), _p(v_pool), _p(block_table), _p(cache_len),
+                                     _p(path), _p(accept_len), C.c_int32(max_path), _p(dst), _p(status))
+    assert rc == 0
+    return dst, status

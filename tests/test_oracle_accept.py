@@ -284,3 +284,58 @@ def test_commit_path_equals_per_layer_compaction_and_feature_gather():
     kc2, vc2, cl2 = kc.copy(), vc.copy(), cl.copy()
     O.commit_path(kt, vt, kc2, vc2, cl2, path, alen)
     assert np.array_equal(kc2, kc1) and np.array_equal(cl2, cl1)
+
+
+# ------------------------------------------------------------------------------ paged cache
+def _paged_copy_of(cache, cache_len, page_size, rng, spare=3):
+    """Scatter a contiguous cache [B][Hkv][S][D] into a pool through a random block table."""
+    B, Hkv, S, D = cache.shape
+    max_blocks = (S + page_size - 1) // page_size
+    num_pages = B * max_blocks + spare
+    perm = rng.permutation(num_pages)
+    bt = perm[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    pool = rng.standard_normal((num_pages, Hkv, page_size, D)).astype(cache.dtype)     # junk everywhere else
+    for b in range(B):
+        for j in range(S):
+            pool[bt[b, j // page_size], :, j % page_size] = cache[b, :, j]
+    return pool, bt
+
+
+def test_paged_gather_and_paged_compaction_match_the_contiguous_layout():
+    rng = np.random.default_rng(23)
+    B, N, Hkv, D, S, ps = 3, 9, 2, 8, 40, 16
+    kc = rng.standard_normal((B, Hkv, S, D)).astype(np.float32)
+    vc = rng.standard_normal((B, Hkv, S, D)).astype(np.float32)
+    cl = np.array([20, 33, 0], dtype=np.int32)
+    for b in range(B):
+        kc[b, :, cl[b]:] = 0
+        vc[b, :, cl[b]:] = 0
+    kp, bt = _paged_copy_of(kc, cl, ps, rng)
+    vp = np.empty_like(kp)
+    for b in range(B):
+        for j in range(S):
+            vp[bt[b, j // ps], :, j % ps] = vc[b, :, j]
+    # gather inverts the scatter on the valid rows, zero elsewhere
+    g, st = O.paged_gather(kp, bt, cl, S)
+    assert st.tolist() == [0, 0, 0] and np.array_equal(g, kc)
+    # compaction: paged == contiguous, seen through the block table
+    kt = rng.standard_normal((B, N, Hkv, D)).astype(np.float32)
+    vt = rng.standard_normal((B, N, Hkv, D)).astype(np.float32)
+    path = np.array([[0, 2, 5, -1], [0, -1, -1, -1], [0, 1, 3, 7]], dtype=np.int32)
+    alen = np.array([2, 0, 3], dtype=np.int32)
+    kc2, vc2, cl2 = kc.copy(), vc.copy(), cl.copy()
+    d1, s1 = O.kv_compact(kt, vt, kc2, vc2, cl2, path, alen)
+    clp = cl.copy()
+    d2, s2 = O.kv_compact_paged(kt, vt, kp, vp, bt, clp, path, alen)
+    assert np.array_equal(d1, d2) and np.array_equal(s1, s2) and np.array_equal(cl2, clp)
+    gk, _ = O.paged_gather(kp, bt, clp, S)
+    gv, _ = O.paged_gather(vp, bt, clp, S)
+    assert np.array_equal(gk, kc2) and np.array_equal(gv, vc2)
+    # a page id outside the pool flags the sequence and leaves it alone
+    bt_bad = bt.copy()
+    bt_bad[1, 2] = kp.shape[0]
+    g, st = O.paged_gather(kp, bt_bad, clp, S)
+    assert st.tolist() == [0, 2, 0] and (g[1] == 0).all() and np.array_equal(g[0], kc2[0])
+    kp3, clq = kp.copy(), clp.copy()
+    d3, s3 = O.kv_compact_paged(kt, vt, kp3, vp.copy(), bt_bad, clq, path, alen)
+    assert s3.tolist() == [0, 2, 0] and clq[1] == clp[1]
