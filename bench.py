@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--resample", action="store_true",
                     help="also time s4c_accept_resample (sequential rule with the correction token; stochastic "
                          "configs only; reported as accept_resample, not part of the step)")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE",
+                    help="also time s4c_tree_attn_paged with this page size (power of two >= 64) through a shuffled "
+                         "block table (reported as paged_attn)")
     ap.add_argument("--draft-linear", action="store_true",
                     help="also time s4c_draft_linear (Eq. 3) on the config's B*N tokens with hidden size Hq*D "
                          "(bf16 configs; reported as draft_linear, not part of the step)")
@@ -249,6 +252,34 @@ def main():
         L = tv.accept_len.cpu().numpy()
         rec["accept_resample"] = {"ms": float(ms.mean()), "ms_min": float(ms.min()), "dtype": "f64",
                                   "accept_len_mean": float(L.mean()), "accept_len_max": int(L.max())}
+    if args.paged:
+        d, page = copies[0], args.paged
+        max_blocks = -(-cfg.S_cap // page)
+        S_log = max_blocks * page
+        num_pages = cfg.B * max_blocks
+        perm = torch.randperm(num_pages, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
+        bt = perm.view(cfg.B, max_blocks).to(torch.int32).contiguous()
+
+        def to_pool(c):      # [B][Hkv][S_cap][D] -> [num_pages][Hkv][page][D] in block-table order
+            pad = torch.zeros(cfg.B, cfg.Hkv, S_log, cfg.D, dtype=c.dtype, device="cuda")
+            pad[:, :, :cfg.S_cap] = c
+            pages = pad.view(cfg.B, cfg.Hkv, max_blocks, page, cfg.D).permute(0, 2, 1, 3, 4).reshape(num_pages, cfg.Hkv, page, cfg.D)
+            pool = torch.empty_like(pages)
+            pool[perm.long()] = pages
+            return pool
+
+        kp, vp = to_pool(d["k_cache"]), to_pool(d["v_cache"])
+        tvp = TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, S_log, cfg.V, d["q"].dtype, cfg.levels, cfg.P)
+        d["cache_len"].copy_(cache_len0)
+        run_p = lambda: B.s4c_tree_attn_paged(d["q"], d["k_tree"], d["v_tree"], kp, vp, bt, d["cache_len"], d["parent"], cfg.P,
+                                              tvp.out, 0.0, tvp.attn_status, tvp.attn_ws)
+        t_p = min(_timed_ms(torch, run_p, reps=max(3, args.steps // 2)) for _ in range(3))
+        tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+        torch.cuda.synchronize()
+        rec["paged_attn"] = {"page_size": page, "ms": t_p, "contiguous_ms": t_attn * 1e3,
+                             "same_bits_as_contiguous": bool(torch.equal(tvp.out.view(torch.int16), tv.out.view(torch.int16)))
+                             if cfg.dtype == "bf16" else None}
+        del kp, vp
     if args.draft_linear and cfg.dtype == "bf16":
         Tn, Hd = cfg.B * cfg.N, cfg.Hq * cfg.D
         g = torch.Generator(device="cuda").manual_seed(1)

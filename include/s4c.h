@@ -87,6 +87,20 @@ s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void*
                          float scale, void* out, int32_t* status, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* s4c_tree_attn over a paged cache (a serving layout; the paper's reuse step does not fix one).
+ *   k_pool, v_pool  [num_pages][Hkv][page_size][D]; page_size a power of two >= 64
+ *   block_table     [B][max_blocks]: cache row j of sequence b is row j % page_size of page
+ *                   block_table[b][j / page_size]; one table serves K and V
+ *   shape->S_cap    must equal max_blocks * page_size (the logical capacity of a sequence)
+ *   A sequence one of whose pages below cache_len[b] is outside [0, num_pages) is flagged
+ *   S4C_SEQ_BAD_LEN and gets an all-zero output.  Everything else as s4c_tree_attn (same
+ *   workspace size, same results bit for bit as on the equivalent contiguous cache). */
+s4c_status s4c_tree_attn_paged(const s4c_attn_shape* shape, const void* q, const void* k_tree, const void* v_tree,
+                               const void* k_pool, const void* v_pool, const int32_t* block_table,
+                               int32_t max_blocks, int32_t page_size, int32_t num_pages, const int32_t* cache_len,
+                               const int32_t* parent, int32_t max_cache_len, float scale, void* out,
+                               int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of device workspace s4c_accept_path needs (per-row partial statistics). */
 size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V);
 
@@ -183,6 +197,16 @@ s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const
                           void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
                           const int32_t* accept_len, int32_t max_path, int32_t* dst_index,
                           int32_t* status, void* hip_stream);
+
+/* s4c_kv_compact into a paged cache (layout as in s4c_tree_attn_paged; shape->S_cap is ignored, the
+ * capacity is max_blocks * page_size).  The pages of rows cache_len[b] .. cache_len[b] + accept_len[b]
+ * must already be in the block table; a page id outside [0, num_pages) flags the sequence
+ * (S4C_SEQ_BAD_LEN) and leaves it untouched. */
+s4c_status s4c_kv_compact_paged(const s4c_attn_shape* shape, const void* k_tree, const void* v_tree, void* k_pool,
+                                void* v_pool, const int32_t* block_table, int32_t max_blocks, int32_t page_size,
+                                int32_t num_pages, int32_t* cache_len, const int32_t* path,
+                                const int32_t* accept_len, int32_t max_path, int32_t* dst_index, int32_t* status,
+                                void* hip_stream);
 
 /* The same for every layer of a model in one call, plus the accepted nodes' feature rows (Sec. 3.2,
  * last paragraph: the accepted tokens and their features are kept for the next drafting phase).

@@ -21,7 +21,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_draft_linear", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
+           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
 
 
 class S4CError(RuntimeError):
@@ -73,6 +73,12 @@ def lib() -> C.CDLL:
         L.s4c_build_tree.restype = C.c_int
         L.s4c_build_tree.argtypes = [C.c_int32] * 4 + [C.c_float] + [C.c_void_p] * 3 + [C.c_int32] + [
             C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_tree_attn_paged.restype = C.c_int
+        L.s4c_tree_attn_paged.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 6 + [C.c_int32] * 3 + [C.c_void_p] * 2 + [
+            C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.s4c_kv_compact_paged.restype = C.c_int
+        L.s4c_kv_compact_paged.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3 + [
+            C.c_int32] + [C.c_void_p] * 3
         L.s4c_draft_linear.restype = C.c_int
         L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6
         L.s4c_probe_stream_read.restype = C.c_int
@@ -150,6 +156,48 @@ def s4c_tree_attn(q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, max_ca
                                _ptr(cache_len), _ptr(parent), int(max_cache_len), float(scale), _ptr(out),
                                _ptr(status), _ptr(workspace), ws_bytes, _stream()))
     return out
+
+
+def s4c_tree_attn_paged(q, k_tree, v_tree, k_pool, v_pool, block_table, cache_len, parent, max_cache_len: int,
+                        out: torch.Tensor, scale: float = 0.0, status: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Tree-masked attention over a paged cache: pools [num_pages][Hkv][page_size][D], block_table [B][max_blocks]."""
+    B, N, Hq, D = q.shape
+    num_pages, Hkv, page_size, _ = k_pool.shape
+    max_blocks = int(block_table.shape[1])
+    if tuple(k_tree.shape) != (B, N, Hkv, D) or v_tree.shape != k_tree.shape or v_pool.shape != k_pool.shape or \
+            k_pool.shape[3] != D or out.shape != q.shape or tuple(block_table.shape) != (B, max_blocks):
+        raise ValueError("inconsistent shapes")
+    for t in (k_tree, v_tree, k_pool, v_pool, out):
+        if t.dtype != q.dtype:
+            raise TypeError("q/k/v/pools/out must share one dtype")
+    for t in (block_table, cache_len, parent):
+        if t.dtype != torch.int32:
+            raise TypeError("block_table / cache_len / parent must be int32")
+    shape = AttnShape(B, Hq, Hkv, D, N, max_blocks * page_size, _dtype_code(q))
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().s4c_tree_attn_paged(C.byref(shape), _ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool), _ptr(v_pool),
+                                     _ptr(block_table), max_blocks, int(page_size), int(num_pages), _ptr(cache_len),
+                                     _ptr(parent), int(max_cache_len), float(scale), _ptr(out), _ptr(status),
+                                     _ptr(workspace), ws_bytes, _stream()))
+    return out
+
+
+def s4c_kv_compact_paged(k_tree, v_tree, k_pool, v_pool, block_table, cache_len, path, accept_len,
+                         dst_index: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> None:
+    B, N, Hkv, D = k_tree.shape
+    num_pages, _, page_size, _ = k_pool.shape
+    max_blocks = int(block_table.shape[1])
+    if tuple(k_pool.shape) != (num_pages, Hkv, page_size, D) or v_tree.shape != k_tree.shape or v_pool.shape != k_pool.shape:
+        raise ValueError("inconsistent shapes")
+    for t in (block_table, cache_len, path, accept_len):
+        if t.dtype != torch.int32:
+            raise TypeError("block_table / cache_len / path / accept_len must be int32")
+    shape = AttnShape(B, Hkv, Hkv, D, N, max_blocks * page_size, _dtype_code(k_tree))
+    _check(lib().s4c_kv_compact_paged(C.byref(shape), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool), _ptr(v_pool),
+                                      _ptr(block_table), max_blocks, int(page_size), int(num_pages), _ptr(cache_len),
+                                      _ptr(path), _ptr(accept_len), int(path.shape[1]), _ptr(dst_index), _ptr(status),
+                                      _stream()))
 
 
 def s4c_accept_path_workspace_size(B: int, N: int, V: int) -> int:

@@ -51,6 +51,10 @@ struct AttnArgs {
     int32_t chunk;    // prefix keys per split (multiple of the key tile)
     int32_t mtiles;   // query-row tiles per (sequence, KV head); set by the launcher
     float scale_log2; // softmax scale * log2(e)
+    // paged cache (block_table != null): k_cache / v_cache are pools [num_pages][Hkv][page][D],
+    // row j of sequence b is row j & (page-1) of page block_table[b][j >> page_shift]
+    const int32_t* block_table;   // [B][max_blocks] or null
+    int32_t max_blocks, page_shift, num_pages;
 };
 
 // launchers (defined in the kernel translation units); return hipGetLastError()
@@ -118,6 +122,8 @@ struct CompactArgs {
     int32_t* status;
     int32_t B, Hkv, N, S_cap, max_path;
     int32_t row_bytes;   // D * element size
+    const int32_t* block_table;   // paged cache: [B][max_blocks] (S_cap = max_blocks << page_shift), else null
+    int32_t max_blocks, page_shift, num_pages;
 };
 hipError_t launch_compact(const CompactArgs& a, hipStream_t st);
 

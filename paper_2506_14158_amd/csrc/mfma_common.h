@@ -39,6 +39,14 @@ __device__ __forceinline__ const unsigned char* uniform(const unsigned char* p) 
     return (const unsigned char*)(((uint64_t)hi << 32) | lo);
 }
 
+// Wave-uniform read-only 32-bit load through the scalar data path.  The tile loops count their
+// direct-to-LDS loads in vmcnt by hand, so a lookup inside them must not be a vector load.
+__device__ __forceinline__ int32_t scalar_load_i32(const void* base, uint32_t byte_off) {
+    int32_t v;
+    asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(base), "s"(byte_off) : "memory");
+    return v;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");

@@ -101,11 +101,19 @@ int32_t s4c_tree_attn_num_splits(const s4c_attn_shape* shape, int32_t max_cache_
     return plan_attn(*shape, max_cache_len).splits;
 }
 
-s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void* k_tree,
-                         const void* v_tree, const void* k_cache, const void* v_cache,
-                         const int32_t* cache_len, const int32_t* parent, int32_t max_cache_len,
-                         float scale, void* out, int32_t* status, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+namespace {
+// log2 of a page size that is a power of two >= 64, else -1
+int page_shift_of(int32_t page_size) {
+    for (int sh = 6; sh < 31; ++sh)
+        if (page_size == (1 << sh)) return sh;
+    return -1;
+}
+
+s4c_status tree_attn_impl(const s4c_attn_shape* shape, const void* q, const void* k_tree, const void* v_tree,
+                          const void* k_cache, const void* v_cache, const int32_t* block_table, int32_t max_blocks,
+                          int32_t page_shift, int32_t num_pages, const int32_t* cache_len, const int32_t* parent,
+                          int32_t max_cache_len, float scale, void* out, int32_t* status, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
     if (!shape || !q || !k_tree || !v_tree || !cache_len || !parent || !out) return S4C_ERR_NULL;
     s4c_status why;
     if (!shape_ok(shape, &why)) return why;
@@ -124,6 +132,7 @@ s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void*
     a.S_cap = shape->S_cap; a.G = shape->Hq / shape->Hkv; a.M = a.N * a.G;
     a.max_cache_len = max_cache_len; a.splits = p.splits; a.chunk = p.chunk;
     a.scale_log2 = (scale > 0.f ? scale : 1.0f / sqrtf((float)shape->D)) * kLog2e;
+    a.block_table = block_table; a.max_blocks = max_blocks; a.page_shift = page_shift; a.num_pages = num_pages;
 
     hipStream_t st = (hipStream_t)hip_stream;
     // Splits are combined by a second kernel: the kernel boundary is what makes one workgroup's
@@ -131,6 +140,30 @@ s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void*
     hipError_t e = p.mfma ? launch_tree_attn_mfma(a, st) : launch_tree_attn_generic(a, shape->dtype, st);
     if (e == hipSuccess && p.splits > 1) e = launch_attn_merge(a, shape->dtype, st);
     return e == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+}  // namespace
+
+s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void* k_tree,
+                         const void* v_tree, const void* k_cache, const void* v_cache,
+                         const int32_t* cache_len, const int32_t* parent, int32_t max_cache_len,
+                         float scale, void* out, int32_t* status, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    return tree_attn_impl(shape, q, k_tree, v_tree, k_cache, v_cache, nullptr, 0, 0, 0, cache_len, parent, max_cache_len,
+                          scale, out, status, workspace, workspace_bytes, hip_stream);
+}
+
+s4c_status s4c_tree_attn_paged(const s4c_attn_shape* shape, const void* q, const void* k_tree, const void* v_tree,
+                               const void* k_pool, const void* v_pool, const int32_t* block_table,
+                               int32_t max_blocks, int32_t page_size, int32_t num_pages, const int32_t* cache_len,
+                               const int32_t* parent, int32_t max_cache_len, float scale, void* out,
+                               int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!shape || !block_table || !k_pool || !v_pool) return S4C_ERR_NULL;
+    const int sh = page_shift_of(page_size);
+    if (sh < 0) return S4C_ERR_UNSUPPORTED;
+    if (max_blocks <= 0 || num_pages <= 0 || (long long)max_blocks * page_size > 0x7FFFFFFFll) return S4C_ERR_SHAPE;
+    if (shape->S_cap != max_blocks * page_size) return S4C_ERR_SHAPE;       // the logical capacity of a sequence
+    return tree_attn_impl(shape, q, k_tree, v_tree, k_pool, v_pool, block_table, max_blocks, sh, num_pages, cache_len,
+                          parent, max_cache_len, scale, out, status, workspace, workspace_bytes, hip_stream);
 }
 
 size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V) {
@@ -231,6 +264,33 @@ s4c_status s4c_kv_compact(const s4c_attn_shape* shape, const void* k_tree, const
     a.cache_len = cache_len; a.path = path; a.accept_len = accept_len; a.dst_index = dst_index;
     a.status = status; a.B = s.B; a.Hkv = s.Hkv; a.N = s.N; a.S_cap = s.S_cap; a.max_path = max_path;
     a.row_bytes = s.D * (s.dtype == S4C_F32 ? 4 : 2);
+    a.block_table = nullptr; a.max_blocks = a.page_shift = a.num_pages = 0;
+    return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+
+s4c_status s4c_kv_compact_paged(const s4c_attn_shape* shape, const void* k_tree, const void* v_tree, void* k_pool,
+                                void* v_pool, const int32_t* block_table, int32_t max_blocks, int32_t page_size,
+                                int32_t num_pages, int32_t* cache_len, const int32_t* path,
+                                const int32_t* accept_len, int32_t max_path, int32_t* dst_index, int32_t* status,
+                                void* hip_stream) {
+    if (!shape || !k_tree || !v_tree || !k_pool || !v_pool || !block_table || !cache_len || !path || !accept_len)
+        return S4C_ERR_NULL;
+    const int sh = page_shift_of(page_size);
+    if (sh < 0) return S4C_ERR_UNSUPPORTED;
+    if (max_blocks <= 0 || num_pages <= 0 || (long long)max_blocks * page_size > 0x7FFFFFFFll) return S4C_ERR_SHAPE;
+    s4c_attn_shape s = *shape;
+    s.S_cap = max_blocks * page_size;
+    if (s.Hq <= 0) s.Hq = s.Hkv;
+    if (s.Hkv > 0 && s.Hq % s.Hkv != 0) s.Hq = s.Hkv;
+    s4c_status why;
+    if (!shape_ok(&s, &why)) return why;
+    if (max_path <= 0) return S4C_ERR_SHAPE;
+    CompactArgs a;
+    a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_pool; a.v_cache = v_pool;
+    a.cache_len = cache_len; a.path = path; a.accept_len = accept_len; a.dst_index = dst_index;
+    a.status = status; a.B = s.B; a.Hkv = s.Hkv; a.N = s.N; a.S_cap = s.S_cap; a.max_path = max_path;
+    a.row_bytes = s.D * (s.dtype == S4C_F32 ? 4 : 2);
+    a.block_table = block_table; a.max_blocks = max_blocks; a.page_shift = sh; a.num_pages = num_pages;
     return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 

@@ -46,7 +46,18 @@ __global__ __launch_bounds__(kThreads) void tree_attn_generic_kernel(AttnArgs a)
     }
     bad_tree = __syncthreads_or(bad_tree);
     const int P = a.cache_len[b];
-    const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    const bool paged = a.block_table != nullptr;
+    if (paged) {
+        // every page the prefix touches must be a page of the pool
+        int bad_page = 0;
+        if (!bad_len)
+            for (int i = tid; i < ((P + (1 << a.page_shift) - 1) >> a.page_shift); i += kThreads) {
+                const int id = a.block_table[(size_t)b * a.max_blocks + i];
+                bad_page |= (id < 0 || id >= a.num_pages);
+            }
+        bad_len |= __syncthreads_or(bad_page);
+    }
     if (a.status && tid == 0 && blockIdx.x == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
     const bool bad = bad_tree || bad_len;
@@ -96,6 +107,16 @@ __global__ __launch_bounds__(kThreads) void tree_attn_generic_kernel(AttnArgs a)
         const bool tree = t >= n_prefix_tiles;
         const int k0 = tree ? (t - n_prefix_tiles) * kBN : kb + t * kBN;
         const int kend = tree ? N : ke;
+        // paged cache: the tile's 32 rows lie in one page (pages are powers of two >= 64 rows)
+        const T* kcp = kc;
+        const T* vcp = vc;
+        size_t krow0 = (size_t)k0;
+        if (paged && !tree) {
+            const int id = a.block_table[(size_t)b * a.max_blocks + (k0 >> a.page_shift)];
+            krow0 = (((size_t)id * a.Hkv + kvh) << a.page_shift) + (size_t)(k0 & ((1 << a.page_shift) - 1));
+            kcp = (const T*)a.k_cache;
+            vcp = (const T*)a.v_cache;
+        }
         // ---- load K and V tile
         for (int e = tid; e < kBN * D; e += kThreads) {
             const int c = e / D, d = e % D;
@@ -107,9 +128,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_generic_kernel(AttnArgs a)
                     kvv = to_f32<T>(kt[off]);
                     vvv = to_f32<T>(vt[off]);
                 } else {
-                    const size_t off = (size_t)kk * D + d;
-                    kvv = to_f32<T>(kc[off]);
-                    vvv = to_f32<T>(vc[off]);
+                    const size_t off = (krow0 + c) * D + d;
+                    kvv = to_f32<T>(kcp[off]);
+                    vvv = to_f32<T>(vcp[off]);
                 }
             }
             Ks[c][d] = kvv;

@@ -38,7 +38,7 @@ constexpr int kStageB = 2 * kTileB;         // K then V
 constexpr int lds_bytes_for(int ns) { return ns * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
 
 
-template <int WR, int NS, int WPE>
+template <int WR, int NS, int WPE, bool PAGED>
 __global__ __launch_bounds__(WR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void tree_attn_mfma_kernel(AttnArgs a) {
     constexpr int NT = WR * 64;
@@ -76,7 +76,18 @@ void tree_attn_mfma_kernel(AttnArgs a) {
     }
     bad_tree = __syncthreads_or(bad_tree);
     const int P = a.cache_len[b];
-    const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    if constexpr (PAGED) {
+        // every page the prefix touches must be a page of the pool (each workgroup checks them all,
+        // so all workgroups of the sequence agree)
+        int bad_page = 0;
+        if (!bad_len)
+            for (int i = tid; i < ((P + (1 << a.page_shift) - 1) >> a.page_shift); i += NT) {
+                const int id = a.block_table[(size_t)b * a.max_blocks + i];
+                bad_page |= (id < 0 || id >= a.num_pages);
+            }
+        bad_len |= __syncthreads_or(bad_page);
+    }
     if (a.status && tid == 0 && member == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
     // wave-uniform by construction; tell the compiler so that everything derived from it stays scalar
@@ -122,8 +133,21 @@ void tree_attn_mfma_kernel(AttnArgs a) {
     const int n_tree = (!bad && sp == a.splits - 1) ? (N + kBN - 1) / kBN : 0;
     const int n_tiles = n_pref + n_tree;
 
+    // cache rows kb + j of this (sequence, KV head): contiguous, or looked up page by page (a tile
+    // never straddles pages: pages are powers of two >= the tile)
     const unsigned char* kc = (const unsigned char*)a.k_cache + (((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap + kb) * kRowB;
     const unsigned char* vc = (const unsigned char*)a.v_cache + (((size_t)b * a.Hkv + kvh) * (size_t)a.S_cap + kb) * kRowB;
+    const int32_t* bt_row = PAGED ? a.block_table + (size_t)b * a.max_blocks : nullptr;
+    auto cache_row = [&](const void* pool_or_base, const unsigned char* contiguous, int j) -> const unsigned char* {
+        if constexpr (PAGED) {
+            const int key = uniform(kb + j);
+            const int id = scalar_load_i32(uniform((const unsigned char*)bt_row), (uint32_t)(key >> a.page_shift) * 4u);
+            const size_t row = (((size_t)id * a.Hkv + kvh) << a.page_shift) + (size_t)(key & ((1 << a.page_shift) - 1));
+            return uniform((const unsigned char*)pool_or_base + row * kRowB);
+        } else {
+            return uniform(contiguous + (size_t)j * kRowB);
+        }
+    };
     const unsigned char* kt = (const unsigned char*)a.k_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
     const unsigned char* vt = (const unsigned char*)a.v_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
     const uint32_t tree_stride = (uint32_t)a.Hkv * kRowB;
@@ -142,8 +166,9 @@ void tree_attn_mfma_kernel(AttnArgs a) {
     auto issue_tile = [&](int t) {
         const uint32_t sbase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(t % NS) * kStageB + wave * 1024);
         if (t < n_full) {
-            const unsigned char* kg = uniform(kc + (size_t)t * kTileB);
-            const unsigned char* vg = uniform(vc + (size_t)t * kTileB);
+            const unsigned char* kg = cache_row(a.k_cache, kc, t * kBN);
+            const unsigned char* vg = PAGED ? kg + ((const unsigned char*)a.v_cache - (const unsigned char*)a.k_cache)
+                                            : cache_row(a.v_cache, vc, t * kBN);
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
                 dma16(kg, kvo_k[c], sbase + WR * c * 1024);
@@ -153,13 +178,18 @@ void tree_attn_mfma_kernel(AttnArgs a) {
             const bool tree = t >= n_pref;
             const int k0 = tree ? (t - n_pref) * kBN : t * kBN;             // relative to kb for the prefix
             const int klast = (tree ? N : ke - kb) - 1;
-            const unsigned char* kg = uniform(tree ? kt : kc);
-            const unsigned char* vg = uniform(tree ? vt : vc);
+            // rows are addressed relative to the tile's first row (or the last valid row, if the
+            // tile starts beyond it), which for the prefix fixes the page
+            const int kq = min(k0, klast);
+            const unsigned char* kg = tree ? uniform(kt + (size_t)kq * tree_stride) : cache_row(a.k_cache, kc, kq);
+            const unsigned char* vg = tree ? uniform(vt + (size_t)kq * tree_stride)
+                                           : (PAGED ? kg + ((const unsigned char*)a.v_cache - (const unsigned char*)a.k_cache)
+                                                    : cache_row(a.v_cache, vc, kq));
             const uint32_t rstride = tree ? tree_stride : (uint32_t)kRowB;
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
                 const int row = 4 * (wave + WR * c) + (lane >> 4), pc = lane & 15;
-                const uint32_t roff = (uint32_t)min(k0 + row, klast) * rstride;
+                const uint32_t roff = (uint32_t)(min(k0 + row, klast) - kq) * rstride;
                 dma16(kg, roff + ((pc ^ (row & 15)) << 4), sbase + WR * c * 1024);
                 dma16(vg, roff + ((pc ^ ((row & 3) << 2)) << 4), sbase + WR * c * 1024 + kTileB);
             }
@@ -358,12 +388,12 @@ void tree_attn_mfma_kernel(AttnArgs a) {
 
 int pick_wr(int M) { return M <= 128 ? 4 : 8; }
 
-template <int WR, int NS, int WPE>
+template <int WR, int NS, int WPE, bool PAGED>
 hipError_t launch(const AttnArgs& a, hipStream_t st) {
     constexpr int kLds = lds_bytes_for(NS);
     static bool attr_set = false;     // benign race: the attribute call is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR, NS, WPE>,
+        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR, NS, WPE, PAGED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -372,7 +402,7 @@ hipError_t launch(const AttnArgs& a, hipStream_t st) {
     k.mtiles = (a.M + WR * 32 - 1) / (WR * 32);
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;          // padded to whole XCD rounds
     dim3 grid((unsigned)(units8 * k.mtiles * a.splits)), block(WR * 64);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR, NS, WPE>), grid, block, kLds, st, k);
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR, NS, WPE, PAGED>), grid, block, kLds, st, k);
     return hipGetLastError();
 }
 
@@ -388,7 +418,8 @@ int mfma_rows_per_block(const s4c_attn_shape& s) {
 
 hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st) {
     if (a.M <= 64) return launch_tree_attn_smallm(a, st);
-    return pick_wr(a.M) == 4 ? launch<4, 4, 1>(a, st) : launch<8, 4, 2>(a, st);
+    if (a.block_table) return pick_wr(a.M) == 4 ? launch<4, 4, 1, true>(a, st) : launch<8, 4, 2, true>(a, st);
+    return pick_wr(a.M) == 4 ? launch<4, 4, 1, false>(a, st) : launch<8, 4, 2, false>(a, st);
 }
 
 }  // namespace s4c

@@ -39,7 +39,7 @@ struct Cfg {
     static constexpr int kLdsBytes = (kRingB + kAuxB > kMergeB) ? kRingB + kAuxB : kMergeB;
 };
 
-template <int kKG>
+template <int kKG, bool PAGED>
 __global__ __launch_bounds__(Cfg<kKG>::kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_smallm_kernel(AttnArgs a) {
     constexpr int kRoundB = Cfg<kKG>::kRoundB, kRingB = Cfg<kKG>::kRingB, kWaves = Cfg<kKG>::kWaves;
@@ -70,7 +70,18 @@ void tree_attn_smallm_kernel(AttnArgs a) {
     }
     bad_tree = __syncthreads_or(bad_tree);
     const int P = a.cache_len[b];
-    const int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    int bad_len = (P < 0 || P > a.max_cache_len || P > a.S_cap);
+    if constexpr (PAGED) {
+        // every page the prefix touches must be a page of the pool (each workgroup checks them all,
+        // so all workgroups of the sequence agree)
+        int bad_page = 0;
+        if (!bad_len)
+            for (int i = tid; i < ((P + (1 << a.page_shift) - 1) >> a.page_shift); i += kThreads) {
+                const int id = a.block_table[(size_t)b * a.max_blocks + i];
+                bad_page |= (id < 0 || id >= a.num_pages);
+            }
+        bad_len |= __syncthreads_or(bad_page);
+    }
     if (a.status && tid == 0 && sp == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
     const bool bad = __builtin_amdgcn_readfirstlane((bad_tree || bad_len) ? 1 : 0) != 0;
@@ -123,6 +134,20 @@ void tree_attn_smallm_kernel(AttnArgs a) {
     const unsigned char* kt = (const unsigned char*)a.k_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
     const unsigned char* vt = (const unsigned char*)a.v_tree + ((size_t)b * N * a.Hkv + kvh) * kRowB;
     const uint32_t tree_stride = (uint32_t)a.Hkv * kRowB;
+    // cache row kb + j of this (sequence, KV head): contiguous, or looked up page by page (a tile
+    // never straddles pages: pages are powers of two >= 64 rows)
+    const int32_t* bt_row = PAGED ? a.block_table + (size_t)b * a.max_blocks : nullptr;
+    auto cache_row = [&](const void* pool, const unsigned char* contiguous, int j) -> const unsigned char* {
+        if constexpr (PAGED) {
+            const int key = uniform(kb + j);
+            const int id = scalar_load_i32(uniform((const unsigned char*)bt_row), (uint32_t)(key >> a.page_shift) * 4u);
+            const size_t row = (((size_t)id * a.Hkv + kvh) << a.page_shift) + (size_t)(key & ((1 << a.page_shift) - 1));
+            return uniform((const unsigned char*)pool + row * kRowB);
+        } else {
+            return uniform(contiguous + (size_t)j * kRowB);
+        }
+    };
+    const ptrdiff_t v_minus_k = (const unsigned char*)a.v_cache - (const unsigned char*)a.k_cache;
 
     // ---- direct-to-LDS loads: the two waves of key group kg load tile kg of every round, four
     // 1 KB instructions each for K and for V (instruction ii covers rows 4 ii .. 4 ii + 3).
@@ -136,8 +161,8 @@ void tree_attn_smallm_kernel(AttnArgs a) {
     auto issue_round = [&](int r) {
         const uint32_t sbase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(r & 1) * kRoundB + kg * kTileB + rb * 4096);
         if (r < n_full) {
-            const unsigned char* kgp = uniform(kc + ((size_t)r * kKG + kg) * kTileKB);
-            const unsigned char* vgp = uniform(vc + ((size_t)r * kKG + kg) * kTileKB);
+            const unsigned char* kgp = cache_row(a.k_cache, kc, (r * kKG + kg) * kBN);
+            const unsigned char* vgp = PAGED ? kgp + v_minus_k : cache_row(a.v_cache, vc, (r * kKG + kg) * kBN);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 dma16(kgp, kvo_k[c], sbase + c * 1024);
@@ -147,13 +172,17 @@ void tree_attn_smallm_kernel(AttnArgs a) {
             const bool tree = r >= n_pref;
             const int k0 = (tree ? r - n_pref : r) * kKG * kBN + kg * kBN;     // first row of this tile
             const int klast = max((tree ? N : len) - 1, 0);
-            const unsigned char* kgp = uniform(tree ? kt : kc);
-            const unsigned char* vgp = uniform(tree ? vt : vc);
+            // rows are addressed relative to the tile's first row (or to the last valid row, if the
+            // tile starts beyond it), which for the prefix fixes the page
+            const int kq = min(k0, klast);
+            const unsigned char* kgp = tree ? uniform(kt + (size_t)kq * tree_stride) : cache_row(a.k_cache, kc, kq);
+            const unsigned char* vgp = tree ? uniform(vt + (size_t)kq * tree_stride)
+                                            : (PAGED ? kgp + v_minus_k : cache_row(a.v_cache, vc, kq));
             const uint32_t rstride = tree ? tree_stride : (uint32_t)kRowB;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int row = 4 * (rb * 4 + c) + (lane >> 4), pc = lane & 15;
-                const uint32_t roff = (uint32_t)min(k0 + row, klast) * rstride;     // clamped: in bounds, masked later
+                const uint32_t roff = (uint32_t)(min(k0 + row, klast) - kq) * rstride;   // clamped: in bounds, masked later
                 dma16(kgp, roff + ((pc ^ (row & 15)) << 4), sbase + c * 1024);
                 dma16(vgp, roff + ((pc ^ ((row & 3) << 2)) << 4), sbase + c * 1024 + kTileKB);
             }
@@ -355,23 +384,23 @@ void tree_attn_smallm_kernel(AttnArgs a) {
 
 }  // namespace
 
-template <int KG>
+template <int KG, bool PAGED>
 static hipError_t launch_smallm(const AttnArgs& a, hipStream_t st) {
     static bool attr_set = false;     // benign race: the attribute call is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_smallm_kernel<KG>,
+        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_smallm_kernel<KG, PAGED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<KG>::kLdsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;
     dim3 grid((unsigned)(units8 * a.splits)), block(Cfg<KG>::kThreads);
-    hipLaunchKernelGGL(tree_attn_smallm_kernel<KG>, grid, block, Cfg<KG>::kLdsBytes, st, a);
+    hipLaunchKernelGGL((tree_attn_smallm_kernel<KG, PAGED>), grid, block, Cfg<KG>::kLdsBytes, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_tree_attn_smallm(const AttnArgs& a, hipStream_t st) {
-    return launch_smallm<2>(a, st);
+    return a.block_table ? launch_smallm<2, true>(a, st) : launch_smallm<2, false>(a, st);
 }
 
 }  // namespace s4c

@@ -1,0 +1,142 @@
+"""Paged-cache entry points (s4c_tree_attn_paged, s4c_kv_compact_paged) on the GPU: bit-identical to the
+contiguous entry points on the equivalent cache, within tolerance of the oracle (which defines paged
+attention as attention over the gathered cache), compaction bit-exact against the paged oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import s4c_oracle as O
+from paper_2506_14158_amd import binding as B, synth
+from paper_2506_14158_amd.verify import TreeVerifier
+from tests.util import attn_errors, to_device
+
+pytestmark = pytest.mark.gpu
+C = synth.CONFIGS
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2)}
+
+
+def scatter_to_pool(cache_np, page_size, rng, spare=5):
+    """contiguous [B][Hkv][S][D] -> (pool [num_pages][Hkv][page][D] with junk in unused rows, block_table)"""
+    Bn, Hkv, S, D = cache_np.shape
+    max_blocks = (S + page_size - 1) // page_size
+    num_pages = Bn * max_blocks + spare
+    bt = rng.permutation(num_pages)[:Bn * max_blocks].reshape(Bn, max_blocks).astype(np.int32)
+    pool = rng.integers(0, 2 ** 15, size=(num_pages, Hkv, page_size, D)).astype(cache_np.dtype) if cache_np.dtype == np.uint16 \
+        else rng.standard_normal((num_pages, Hkv, page_size, D)).astype(np.float32)
+    pad = np.zeros((Bn, Hkv, max_blocks * page_size, D), dtype=cache_np.dtype)
+    pad[:, :, :S] = cache_np
+    for b in range(Bn):
+        for p in range(max_blocks):
+            pool[bt[b, p]] = pad[b, :, p * page_size:(p + 1) * page_size]
+    return pool, bt
+
+
+SHAPES = [
+    (synth.scaled(C[1], name="tiny-f32", B=2, P=200, ragged=True, index=0), 64),                    # scalar kernel
+    (synth.scaled(C[2], name="7b-splits", Hq=2, Hkv=2, P=2500, index=0), 128),                      # <= 64 rows, splits
+    (synth.scaled(C[3], name="13b-small", B=2, Hq=3, Hkv=3, P=1000, ragged=True, index=0), 64),
+    (synth.scaled(C[5], name="70b-mid", B=1, Hq=8, Hkv=1, P=300, N=16, levels=5, index=0), 256),    # 128 rows
+    (synth.scaled(C[4], name="gqa-small", B=2, Hq=8, Hkv=2, P=640, index=0), 128),                  # 256 rows
+    (synth.scaled(C[5], name="70b-small", B=2, Hq=16, Hkv=2, P=3000, ragged=True, index=0), 512),   # 1024 rows, ragged
+    (synth.scaled(C[4], name="gqa-p0", B=2, Hq=4, Hkv=1, P=0, N=50, levels=6, index=0), 64),        # empty prefix
+]
+
+
+@pytest.mark.parametrize("cfg,page", SHAPES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_paged_attention_equals_contiguous_and_oracle(cfg, page):
+    rng = np.random.default_rng(page + cfg.N)
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    d = to_device(cfg, par, at)
+    kp, bt = scatter_to_pool(at.k_cache, page, rng)
+    rng2 = np.random.default_rng(page + cfg.N)                     # same permutation for V
+    vp, bt2 = scatter_to_pool(at.v_cache, page, rng2)
+    assert np.array_equal(bt, bt2)
+    dev = lambda a: torch.from_numpy(a).cuda() if a.dtype != np.uint16 else torch.from_numpy(a).view(torch.bfloat16).cuda()
+    S_log = bt.shape[1] * page
+    tv = TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, S_log, cfg.V, d["q"].dtype, cfg.levels, cfg.P)
+    out_p = torch.full_like(tv.out, float("nan"))
+    st = torch.full((cfg.B,), -3, dtype=torch.int32, device="cuda")
+    B.s4c_tree_attn_paged(d["q"], d["k_tree"], d["v_tree"], dev(kp), dev(vp), dev(bt), d["cache_len"], d["parent"], cfg.P,
+                          out_p, 0.0, st, tv.attn_ws)
+    torch.cuda.synchronize()
+    assert st.cpu().tolist() == [0] * cfg.B
+    # contiguous entry point on a cache of the same logical capacity: identical split plan, identical bits
+    kc = torch.zeros(cfg.B, cfg.Hkv, S_log, cfg.D, dtype=d["q"].dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    kc[:, :, :cfg.S_cap] = d["k_cache"]
+    vc[:, :, :cfg.S_cap] = d["v_cache"]
+    tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], kc, vc, d["cache_len"], d["parent"])
+    torch.cuda.synchronize()
+    view = torch.int32 if cfg.dtype == "f32" else torch.int16
+    assert torch.equal(out_p.view(view), tv.out.view(view))
+    # the oracle's definition: attention over the gathered cache
+    gk, s1 = O.paged_gather(kp, bt, at.cache_len, cfg.S_cap)
+    gv, _ = O.paged_gather(vp, bt, at.cache_len, cfg.S_cap)
+    assert (s1 == 0).all()
+    ref, _ = O.tree_attn(at.q, at.k_tree, at.v_tree, gk, gv, at.cache_len, par)
+    amax, rel = attn_errors(out_p, ref)
+    assert amax <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1], (amax, rel)
+
+
+def test_paged_step_compaction_and_bad_pages():
+    cfg = synth.scaled(C[4], name="gqa-small", B=3, Hq=8, Hkv=2, P=300, V=5000, ragged=True, index=0)
+    page = 64
+    rng = np.random.default_rng(4)
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg)
+    ac = synth.make_accept_inputs(cfg, par)
+    d = to_device(cfg, par, at, ac)
+    kp, bt = scatter_to_pool(at.k_cache, page, rng)
+    vp, _ = scatter_to_pool(at.v_cache, page, np.random.default_rng(4))
+    dev = lambda a: torch.from_numpy(a).view(torch.bfloat16).cuda() if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
+    d_kp, d_vp, d_bt = dev(kp), dev(vp), dev(bt)
+    S_log = bt.shape[1] * page
+    tv = TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, S_log, cfg.V, d["q"].dtype, cfg.levels, cfg.P)
+    B.s4c_tree_attn_paged(d["q"], d["k_tree"], d["v_tree"], d_kp, d_vp, d_bt, d["cache_len"], d["parent"], cfg.P, tv.out,
+                          0.0, tv.attn_status, tv.attn_ws)
+    tv.accept_path(d["logits"], d["parent"], d["tokens"], B.S4C_GREEDY)
+    dst = torch.full((cfg.B, cfg.levels), -9, dtype=torch.int32, device="cuda")
+    cst = torch.full((cfg.B,), -9, dtype=torch.int32, device="cuda")
+    cl = d["cache_len"].clone()
+    B.s4c_kv_compact_paged(d["k_tree"], d["v_tree"], d_kp, d_vp, d_bt, cl, tv.path, tv.accept_len, dst, cst)
+    torch.cuda.synchronize()
+    r = O.accept_path(ac.logits, par, ac.tokens, "greedy", cfg.levels)
+    assert np.array_equal(tv.path.cpu().numpy(), r["path"])
+    clo = at.cache_len.copy()
+    d2, s2 = O.kv_compact_paged(at.k_tree, at.v_tree, kp, vp, bt, clo, r["path"], r["accept_len"])   # in place on kp, vp
+    assert np.array_equal(dst.cpu().numpy(), d2) and np.array_equal(cst.cpu().numpy(), s2)
+    assert np.array_equal(cl.cpu().numpy(), clo)
+    assert np.array_equal(d_kp.view(torch.int16).cpu().numpy().view(np.uint16), kp)
+    assert np.array_equal(d_vp.view(torch.int16).cpu().numpy().view(np.uint16), vp)
+    # a page id outside the pool: attention flags the sequence and zeroes it, compaction leaves it alone
+    bt_bad = bt.copy()
+    bt_bad[1, 0] = kp.shape[0] + 7
+    d_btb = dev(bt_bad)
+    B.s4c_tree_attn_paged(d["q"], d["k_tree"], d["v_tree"], d_kp, d_vp, d_btb, d["cache_len"], d["parent"], cfg.P, tv.out,
+                          0.0, tv.attn_status, tv.attn_ws)
+    torch.cuda.synchronize()
+    assert tv.attn_status.cpu().tolist() == [0, B.S4C_SEQ_BAD_LEN, 0] and (tv.out[1] == 0).all()
+    bt_bad2 = bt.copy()
+    bt_bad2[2, int(clo[2]) // page] = -1                      # the page the next accepted rows would go to
+    cl2 = cl.clone()
+    before = d_kp.clone()
+    B.s4c_kv_compact_paged(d["k_tree"], d["v_tree"], d_kp, d_vp, dev(bt_bad2), cl2, tv.path, tv.accept_len, dst, cst)
+    torch.cuda.synchronize()
+    assert cst.cpu().tolist()[2] == B.S4C_SEQ_BAD_LEN and int(cl2[2]) == int(cl[2])
+    clo2 = clo.copy()
+    kp2 = kp.copy()
+    _, s3 = O.kv_compact_paged(at.k_tree, at.v_tree, kp2, vp.copy(), bt_bad2, clo2, r["path"], r["accept_len"])
+    assert np.array_equal(cst.cpu().numpy(), s3) and np.array_equal(cl2.cpu().numpy(), clo2)
+    assert np.array_equal(d_kp.view(torch.int16).cpu().numpy().view(np.uint16), kp2)
+    del before
+
+
+def test_paged_rejects_bad_arguments():
+    t = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
+    i = lambda *s: torch.zeros(*s, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.S4CError):       # page size must be a power of two >= 64
+        B.s4c_tree_attn_paged(t(1, 4, 2, 128), t(1, 4, 1, 128), t(1, 4, 1, 128), t(3, 1, 48, 128), t(3, 1, 48, 128), i(1, 2),
+                              i(1), i(1, 4), 10, t(1, 4, 2, 128))
+    with pytest.raises(B.S4CError):
+        B.s4c_kv_compact_paged(t(1, 4, 1, 128), t(1, 4, 1, 128), t(3, 1, 32, 128), t(3, 1, 32, 128), i(1, 2), i(1), i(1, 3), i(1))
