@@ -4,12 +4,15 @@
 // columns of W against e and the last H against f.
 //
 //   * Both operands have the reduction index contiguous in memory (W is [Hout][2H], e and f are
-//     [T][H]), which is what v_mfma_f32_32x32x16_bf16 wants for A and for B: a lane's 8 values
+//     [T][H]), which is what the matrix-core instruction wants for A and for B: a lane's 8 values
 //     are 16 consecutive bytes of one row.  The product is formed transposed, D = W x^T (A = W
 //     rows, B = token rows), so a lane ends up with 4 consecutive output features of one token
 //     and stores them as one 8-byte word.
+//   * v_mfma_f32_16x16x32_bf16 rather than the 32x32x16 shape: with random operands the chip is
+//     power-limited and the smaller shape sustains a higher clock (measured 7 % faster here); the
+//     wave tile keeps the LDS bytes per FLOP the same.
 //   * Workgroup tile 256 output features x 256 tokens, K step 32; wave (wo, wt) of 8 owns
-//     128 features x 64 tokens = 4 x 2 accumulator blocks.  W and token tiles stream from HBM /
+//     128 features x 64 tokens = 8 x 4 accumulator blocks of 16 x 16.  W and token tiles stream from HBM /
 //     L2 straight into LDS (global_load_lds_dwordx4) through a ring of four 32 KB stages used in
 //     pairs: one barrier per two K steps, the next pair in flight while a pair is multiplied.
 //     (Four waves with 128 x 128 wave tiles, half the fragment reads per MFMA, measured slower.)
@@ -77,51 +80,43 @@ void draft_linear_kernel(LinearArgs a) {
         }
     };
 
-    // ---- fragment addresses inside a stage
-    const int wo = wave / (8 / kTB), wt = wave % (8 / kTB), g32 = lane >> 5, l32 = lane & 31;
-    uint32_t w_off[4][2], x_off[kTB][2];                    // [block][k step]
+    // ---- fragment addresses inside a stage (v_mfma_f32_16x16x32_bf16: a lane supplies row lane % 16,
+    // reduction elements 8 (lane / 16) .. + 7, i.e. chunk lane / 16 of the 64-byte row)
+    const int wo = wave / (8 / kTB), wt = wave % (8 / kTB), g16 = lane >> 4, l16 = lane & 15;
+    uint32_t w_off[8], x_off[2 * kTB];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int c = ks * 2 + g32;
+    for (int ob = 0; ob < 8; ++ob) {
+        const int row = wo * 128 + ob * 16 + l16;
+        w_off[ob] = row * kRow + ((g16 ^ ((row >> 1) & 3)) << 4);
+    }
 #pragma unroll
-        for (int ob = 0; ob < 4; ++ob) {
-            const int row = wo * 128 + ob * 32 + l32;
-            w_off[ob][ks] = row * kRow + ((c ^ ((row >> 1) & 3)) << 4);
-        }
-#pragma unroll
-        for (int tb = 0; tb < kTB; ++tb) {
-            const int row = wt * (32 * kTB) + tb * 32 + l32;
-            x_off[tb][ks] = kHalf + row * kRow + ((c ^ ((row >> 1) & 3)) << 4);
-        }
+    for (int tb = 0; tb < 2 * kTB; ++tb) {
+        const int row = wt * (32 * kTB) + tb * 16 + l16;
+        x_off[tb] = kHalf + row * kRow + ((g16 ^ ((row >> 1) & 3)) << 4);
     }
 
-    f32x16 acc[4][kTB];
+    f32x4 acc[8][2 * kTB];
 #pragma unroll
-    for (int ob = 0; ob < 4; ++ob)
+    for (int ob = 0; ob < 8; ++ob)
 #pragma unroll
-        for (int tb = 0; tb < kTB; ++tb)
+        for (int tb = 0; tb < 2 * kTB; ++tb)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) acc[ob][tb][j] = 0.f;
+            for (int j = 0; j < 4; ++j) acc[ob][tb][j] = 0.f;
 
     // Two K steps per barrier: while the pair (kt, kt+1) is multiplied out of two ring stages, the
     // next pair streams into the other two.
     auto compute = [&](int kt) {
         const lds_u8* stage = (const lds_u8*)smem + (kt % kNS) * kStage;
-        bf16x8 wf[4][2], xf[kTB][2];
+        bf16x8 wf[8], xf[2 * kTB];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ob = 0; ob < 8; ++ob) wf[ob] = *(const lds_bf16x8*)(stage + w_off[ob]);
 #pragma unroll
-            for (int ob = 0; ob < 4; ++ob) wf[ob][ks] = *(const lds_bf16x8*)(stage + w_off[ob][ks]);
+        for (int tb = 0; tb < 2 * kTB; ++tb) xf[tb] = *(const lds_bf16x8*)(stage + x_off[tb]);
 #pragma unroll
-            for (int tb = 0; tb < kTB; ++tb) xf[tb][ks] = *(const lds_bf16x8*)(stage + x_off[tb][ks]);
-        }
+        for (int ob = 0; ob < 8; ++ob)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int ob = 0; ob < 4; ++ob)
-#pragma unroll
-                for (int tb = 0; tb < kTB; ++tb)
-                    acc[ob][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ob][ks], xf[tb][ks], acc[ob][tb], 0, 0, 0);
+            for (int tb = 0; tb < 2 * kTB; ++tb)
+                acc[ob][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ob], xf[tb], acc[ob][tb], 0, 0, 0);
     };
     issue(0);
     issue(1);                                              // nk is even (nk = 2 H / 32)
@@ -133,30 +128,28 @@ void draft_linear_kernel(LinearArgs a) {
         compute(kt + 1);
     }
 
-    // ---- epilogue: lane holds, per block, features 8 (j/4) + 4 g32 + (j%4) of token l32
+    // ---- epilogue: per block a lane holds features 4 (lane / 16) .. + 3 of token lane % 16
     const bf16_t* bias = (const bf16_t*)a.bias;
 #pragma unroll
-    for (int tb = 0; tb < kTB; ++tb) {
-        const int tok = t0 + wt * (32 * kTB) + tb * 32 + l32;
+    for (int tb = 0; tb < 2 * kTB; ++tb) {
+        const int tok = t0 + wt * (32 * kTB) + tb * 16 + l16;
         if (tok >= T) continue;
-        bf16_t* orow = (bf16_t*)a.out + (size_t)tok * a.Hout + o0 + wo * 128 + 4 * g32;
+        bf16_t* orow = (bf16_t*)a.out + (size_t)tok * a.Hout + o0 + wo * 128 + 4 * g16;
 #pragma unroll
-        for (int ob = 0; ob < 4; ++ob)
+        for (int ob = 0; ob < 8; ++ob) {
+            float v[4];
 #pragma unroll
-            for (int jq = 0; jq < 4; ++jq) {
-                float v[4];
+            for (int u = 0; u < 4; ++u) v[u] = acc[ob][tb][u];
+            if (bias) {
+                const bf16_t* bp = bias + o0 + wo * 128 + ob * 16 + 4 * g16;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) v[u] = acc[ob][tb][4 * jq + u];
-                if (bias) {
-                    const bf16_t* bp = bias + o0 + wo * 128 + ob * 32 + 8 * jq + 4 * g32;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) v[u] += bf16_to_f32(bp[u]);
-                }
-                uint2 pk;
-                pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-                pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-                *(uint2*)(orow + ob * 32 + 8 * jq) = pk;
+                for (int u = 0; u < 4; ++u) v[u] += bf16_to_f32(bp[u]);
             }
+            uint2 pk;
+            pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+            pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+            *(uint2*)(orow + ob * 16) = pk;
+        }
     }
 }
 
