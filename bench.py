@@ -351,6 +351,22 @@ def main():
         rec["multi_layer"] = {"layers": Ly, "ms_per_step": ms_model, "steps_per_s": 1e3 / ms_model,
                               "commit_path_ms": ev[0].elapsed_time(ev[1]),
                               "kv_cache_GB": 2 * kcL.numel() * kcL.element_size() / 1e9}
+        if args.graph:
+            # the same whole-model step replayed from one captured HIP graph (no per-launch host work)
+            side = torch.cuda.Stream()
+            gm = torch.cuda.CUDAGraph()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(gm, stream=side):
+                    model_step()
+            gm.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(nsteps):
+                gm.replay()
+            torch.cuda.synchronize()
+            rec["multi_layer"]["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / nsteps
+            del gm
         del kcL, vcL, ktL, vtL
     if args.graph:
         # launch-bound configs: one graph launch instead of six kernel launches per step
