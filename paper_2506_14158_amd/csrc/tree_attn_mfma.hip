@@ -33,6 +33,7 @@ namespace {
 using namespace mfma;
 
 constexpr int kBN = 64;                     // keys per tile
+constexpr float kLazyLog2 = 8.0f;           // full tiles rescale only when a row maximum grew by more than 2^8
 constexpr int kTileB = kBN * kRowB;         // bytes per K (or V) tile: 16 KB
 constexpr int kStageB = 2 * kTileB;         // K then V
 constexpr int lds_bytes_for(int ns) { return ns * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
@@ -277,27 +278,56 @@ void tree_attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int j = 1; j < 16; ++j) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[0][j]), s[1][j]);    // v_max3_f32
         mx = max_across_halves(mx);
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        float m_safe = m_new;
-        if constexpr (MODE == kTree) m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // row with no visible key yet
-        const float alpha = fast_exp2(m_run - m_safe);
         float psum = 0.f;
+        if constexpr (MODE == kPlain) {
+            // Full prefix tiles move the row's reference maximum only when some row of the wave
+            // outgrew it by more than 2^kLazyLog2: until then the exponentials are taken against the
+            // stale reference (they stay below 2^kLazyLog2, exact in fp32 and in bf16's range), and the
+            // 64 multiplications of the output accumulator are skipped.  Sum and accumulator stay
+            // consistent with whatever reference is current, which is all the final division (or the
+            // merge of KV splits) needs.
+            const float mt = mx * a.scale_log2;
+            if (__any(mt > m_run + kLazyLog2)) {
+                const float m_new = fmaxf(m_run, mt);
+                const float alpha = fast_exp2(m_run - m_new);          // first tile: exp2(-inf) = 0
+                l_run *= alpha;
 #pragma unroll
-        for (int kblk = 0; kblk < 2; ++kblk)
+                for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const float p = fast_exp2(fmaf(s[kblk][j], a.scale_log2, -m_safe));
-                s[kblk][j] = p;
-                psum += p;
+                    for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+                m_run = m_new;
             }
-        l_run = l_run * alpha + psum;
-        if (__any(m_new > m_run)) {
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+                for (int j = 0; j < 16; ++j) {
+                    const float p = fast_exp2(fmaf(s[kblk][j], a.scale_log2, -m_run));
+                    s[kblk][j] = p;
+                    psum += p;
+                }
+            l_run += psum;
+        } else {
+            const float m_new = fmaxf(m_run, mx * a.scale_log2);
+            float m_safe = m_new;
+            if constexpr (MODE == kTree) m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // row with no visible key yet
+            const float alpha = fast_exp2(m_run - m_safe);
+#pragma unroll
+            for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float p = fast_exp2(fmaf(s[kblk][j], a.scale_log2, -m_safe));
+                    s[kblk][j] = p;
+                    psum += p;
+                }
+            l_run = l_run * alpha + psum;
+            if (__any(m_new > m_run)) {
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+            }
+            m_run = m_new;
         }
-        m_run = m_new;
 
         // O^T += V^T P^T in four steps of 16 keys; the V^T fragments of step i+1 are requested
         // before the MFMAs of step i.
