@@ -107,6 +107,9 @@ def main():
                     help="also time the step replayed from a captured HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 3 plain 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--constant-data", action="store_true",
+                    help="also time s4c_tree_attn with every Q/K/V element set to 0.5 (same launches, same instruction "
+                         "stream; reported as attn_constant_data: shows how much of the time is the data-dependent clock)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the step has no cross-GPU part); use --gpus 1", file=sys.stderr)
@@ -386,6 +389,18 @@ def main():
             g.replay()
         torch.cuda.synchronize()
         rec["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / (reps * ncopy)
+    if args.constant_data:
+        # last GPU leg: it overwrites the inputs of copy 0
+        d = copies[0]
+        d["cache_len"].copy_(cache_len0)
+        for name in ("q", "k_tree", "v_tree", "k_cache", "v_cache"):
+            d[name].fill_(0.5)
+        run = lambda: tv.tree_attn(d["q"], d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
+        for _ in range(max(1, args.warmup)):
+            run()
+        ms = _timed_ms(torch, run, reps=max(3, min(args.steps, 20)))
+        rec["attn_constant_data"] = {"ms": ms, "TFLOPs": flops / ms / 1e9, "GBps": kv_bytes / ms / 1e6,
+                                     "note": "every Q/K/V element 0.5; compare phases_ms.tree_attn (seeded N(0,1) data)"}
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, par, at, ac)
     print(json.dumps(rec))

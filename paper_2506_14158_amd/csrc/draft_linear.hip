@@ -160,12 +160,9 @@ int draft_linear_tile_k() { return kBK; }
 
 hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st) {
     constexpr int kLds = kNS * kStage;
-    static bool attr_set = false;     // benign race: the attribute call is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)draft_linear_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    const hipError_t ea = ensure_dynamic_lds((const void*)draft_linear_kernel, kLds, lds_set);
+    if (ea != hipSuccess) return ea;
     LinearArgs k = a;
     k.ttiles = (a.T + kBT - 1) / kBT;
     k.otiles = a.Hout / kBO;

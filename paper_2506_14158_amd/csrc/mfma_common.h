@@ -1,6 +1,7 @@
 // Helpers shared by the matrix-core attention kernels (gfx950): vector types, direct-to-LDS
 // loads with manual vmcnt tracking, uniform-value hints, cross-half max.
 #pragma once
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -61,4 +62,18 @@ __device__ __forceinline__ float max_across_halves(float x) {
 }
 
 }  // namespace mfma
+
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy
+// of the function).  `done` is a bit per device ordinal; concurrent first calls both set the
+// attribute, which is idempotent.
+inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_relaxed) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_relaxed);
+    return e;
+}
 }  // namespace s4c

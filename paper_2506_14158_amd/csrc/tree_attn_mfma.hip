@@ -421,13 +421,9 @@ int pick_wr(int M) { return M <= 128 ? 4 : 8; }
 template <int WR, int NS, int WPE, bool PAGED>
 hipError_t launch(const AttnArgs& a, hipStream_t st) {
     constexpr int kLds = lds_bytes_for(NS);
-    static bool attr_set = false;     // benign race: the attribute call is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_mfma_kernel<WR, NS, WPE, PAGED>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_mfma_kernel<WR, NS, WPE, PAGED>, kLds, lds_set);
+    if (ea != hipSuccess) return ea;
     AttnArgs k = a;
     k.mtiles = (a.M + WR * 32 - 1) / (WR * 32);
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;          // padded to whole XCD rounds

@@ -386,13 +386,9 @@ void tree_attn_smallm_kernel(AttnArgs a) {
 
 template <int KG, bool PAGED>
 static hipError_t launch_smallm(const AttnArgs& a, hipStream_t st) {
-    static bool attr_set = false;     // benign race: the attribute call is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)tree_attn_smallm_kernel<KG, PAGED>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<KG>::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_smallm_kernel<KG, PAGED>, Cfg<KG>::kLdsBytes, lds_set);
+    if (ea != hipSuccess) return ea;
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;
     dim3 grid((unsigned)(units8 * a.splits)), block(Cfg<KG>::kThreads);
     hipLaunchKernelGGL((tree_attn_smallm_kernel<KG, PAGED>), grid, block, Cfg<KG>::kLdsBytes, st, a);
