@@ -12,8 +12,19 @@
 #include <omp.h>
 #endif
 
+/* IEEE 754 binary16 (1 sign, 5 exponent, 10 fraction bits) -> double, by its definition */
+static double half_to_double(uint16_t h) {
+    const int sign = (h >> 15) & 1, e = (h >> 10) & 0x1F, frac = h & 0x3FF;
+    double v;
+    if (e == 0) v = ldexp((double)frac, -24);                       /* zero and subnormals: frac * 2^-24 */
+    else if (e == 31) v = frac ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)frac / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void* base, int32_t dtype, size_t idx) {
     if (dtype == 0) return (double)((const float*)base)[idx];
+    if (dtype == 2) return half_to_double(((const uint16_t*)base)[idx]);
     uint32_t bits = ((uint32_t)((const uint16_t*)base)[idx]) << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -21,6 +32,12 @@ static double load_elem(const void* base, int32_t dtype, size_t idx) {
 }
 
 static size_t elem_size(int32_t dtype) { return dtype == 0 ? 4 : 2; }
+
+/* test hook: decode n stored elements to double */
+int oracle_decode(int32_t dtype, int32_t n, const void* src, double* dst) {
+    for (int32_t i = 0; i < n; ++i) dst[i] = load_elem(src, dtype, (size_t)i);
+    return 0;
+}
 
 int oracle_num_threads(void) {
 #ifdef _OPENMP

@@ -7,7 +7,8 @@
  * double precision.  It shares no code with the HIP library and must never be called from
  * the product path; only tests, the smoke check and the benchmark's cpu_baseline leg use it.
  *
- * Every pointer is a HOST pointer.  dtype: 0 = fp32, 1 = bf16 stored as uint16 bit patterns.
+ * Every pointer is a HOST pointer.  dtype: 0 = fp32, 1 = bf16 stored as uint16 bit patterns,
+ * 2 = fp16 (IEEE binary16, the precision of the paper's experiments, Sec. 4.1) as uint16 bit patterns.
  * Layouts (row-major, innermost last):
  *   q, out       [B][N][Hq][D]        k_tree, v_tree [B][N][Hkv][D]
  *   k_cache, v_cache [B][Hkv][S_cap][D]   cache_len [B]   parent [B][N]
@@ -32,6 +33,10 @@ extern "C" {
 typedef struct {
     int32_t B, Hq, Hkv, D, N, S_cap, dtype;
 } oracle_shape;
+
+/* Decodes n stored elements of the given dtype to double (exposed so the element decoding can be
+ * pinned on its own). */
+int oracle_decode(int32_t dtype, int32_t n, const void* src, double* dst);
 
 /* status bits written per sequence */
 #define ORACLE_BAD_TREE 1

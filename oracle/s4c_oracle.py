@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged", "oracle_decode"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -49,7 +49,17 @@ def _dt(a: np.ndarray) -> int:
         return 0
     if a.dtype == np.uint16:
         return 1
-    raise TypeError("oracle arrays must be float32 or uint16 (bf16 bits), got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return 2
+    raise TypeError("oracle arrays must be float32, uint16 (bf16 bits) or float16, got %s" % a.dtype)
+
+
+def decode(a: np.ndarray) -> np.ndarray:
+    """Stored elements (float32 / bf16 bits as uint16 / float16) -> the doubles the oracle computes with."""
+    a = np.ascontiguousarray(a)
+    out = np.empty(a.size, dtype=np.float64)
+    _load().oracle_decode(_dt(a), a.size, _p(a), _p(out))
+    return out.reshape(a.shape)
 
 
 def _p(a):

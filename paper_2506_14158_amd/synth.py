@@ -40,7 +40,7 @@ class VerifyConfig:
     Hq: int
     Hkv: int
     D: int
-    dtype: str                 # "f32" | "bf16"  (Q/K/V/cache/logits storage type)
+    dtype: str                 # "f32" | "bf16" | "f16"  (Q/K/V/cache/logits storage type)
     P: int                     # prefix length (cache_len[b] unless ragged)
     N: int                     # tree nodes including the root
     levels: int                # node levels including the root
@@ -97,16 +97,25 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def storage_type(dtype: str):
+    """numpy element type of a config dtype: fp32 and fp16 natively, bf16 as uint16 bit patterns."""
+    return {"f32": np.float32, "bf16": np.uint16, "f16": np.float16}[dtype]
+
+
 def stored(x_f32: np.ndarray, dtype: str) -> np.ndarray:
-    """fp32 draw -> storage array of the config dtype."""
+    """fp32 draw -> storage array of the config dtype (round to nearest even)."""
     if dtype == "f32":
         return np.ascontiguousarray(x_f32, dtype=np.float32)
+    if dtype == "f16":
+        return np.ascontiguousarray(x_f32, dtype=np.float32).astype(np.float16)
     return f32_to_bf16_bits(x_f32)
 
 
 def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
     """storage array -> exact fp32 values."""
-    return x if dtype == "f32" else bf16_bits_to_f32(x)
+    if dtype == "f32":
+        return x
+    return x.astype(np.float32) if dtype == "f16" else bf16_bits_to_f32(x)
 
 
 def _rng(seed: int, comp: int, b: int = 0) -> np.random.Generator:
@@ -205,7 +214,7 @@ def _normal(seed, comp, b, shape, std, dtype):
 
 def make_attn_inputs(cfg: VerifyConfig, seed: Optional[int] = None, threads: int = 8) -> AttnInputs:
     seed = cfg.seed() if seed is None else seed
-    st = np.float32 if cfg.dtype == "f32" else np.uint16
+    st = storage_type(cfg.dtype)
     B, N, Hq, Hkv, D, S = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, cfg.S_cap
     if cfg.ragged:
         cache_len = _rng(seed, _C_KCACHE, 10_000).integers(cfg.P // 2, cfg.P + 1, size=B).astype(np.int32)
@@ -261,7 +270,7 @@ def make_accept_inputs(cfg: VerifyConfig, parent: np.ndarray, seed: Optional[int
     """full_draft (stochastic mode only): also keep every internal node's whole draft
     distribution and draw the uniforms of the correction token; the other arrays are unchanged."""
     seed = cfg.seed() if seed is None else seed
-    st = np.float32 if cfg.dtype == "f32" else np.uint16
+    st = storage_type(cfg.dtype)
     B, N, V = cfg.B, cfg.N, cfg.V
     logits = np.empty((B, N, V), dtype=st)
     tokens = np.zeros((B, N), dtype=np.int32)
