@@ -107,6 +107,9 @@ def main():
                     help="also time the step replayed from a captured HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 3 plain 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--dtype", choices=("config", "bf16", "f16"), default="config",
+                    help="storage type of Q/K/V/cache/logits: the config's own (bf16 for configs 2-5), or fp16, the "
+                         "precision of the paper's experiments (Sec. 4.1); a non-default choice is named in config.workload")
     ap.add_argument("--constant-data", action="store_true",
                     help="also time s4c_tree_attn with every Q/K/V element set to 0.5 (same launches, same instruction "
                          "stream; reported as attn_constant_data: shows how much of the time is the data-dependent clock)")
@@ -123,6 +126,11 @@ def main():
 
     B.lib()   # fail loudly if the HIP library is not built
     cfg = synth.CONFIGS[args.config]
+    if args.dtype != "config" and args.dtype != cfg.dtype:
+        if cfg.dtype == "f32":
+            print("bench.py: config %d is an fp32 workload" % args.config, file=sys.stderr)
+            sys.exit(2)
+        cfg = synth.scaled(cfg, dtype=args.dtype)
     par = synth.make_parent(cfg)
     at = synth.make_attn_inputs(cfg, threads=16)
     resample = args.resample and cfg.mode == "stochastic"
@@ -180,7 +188,7 @@ def main():
     flops = 4.0 * cfg.B * cfg.Hq * cfg.N * (cfg.P + cfg.N) * cfg.D
     logits_bytes = cfg.B * cfg.N * cfg.V * es
     ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
-    if cfg.dtype == "bf16" and flops / kv_bytes > ridge:
+    if cfg.dtype in ("bf16", "f16") and flops / kv_bytes > ridge:
         roof = {"bound": "mfma", "achieved": flops / t_attn / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": kv_bytes / t_attn / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
@@ -281,16 +289,17 @@ def main():
         torch.cuda.synchronize()
         rec["paged_attn"] = {"page_size": page, "ms": t_p, "contiguous_ms": t_attn * 1e3,
                              "same_bits_as_contiguous": bool(torch.equal(tvp.out.view(torch.int16), tv.out.view(torch.int16)))
-                             if cfg.dtype == "bf16" else None}
+                             if cfg.dtype != "f32" else None}
         del kp, vp
-    if args.draft_linear and cfg.dtype == "bf16":
+    if args.draft_linear and cfg.dtype != "f32":
+        dt_ = d0["q"].dtype
         Tn, Hd = cfg.B * cfg.N, cfg.Hq * cfg.D
         g = torch.Generator(device="cuda").manual_seed(1)
         rn = lambda *s_: torch.randn(*s_, device="cuda", generator=g)
-        e_, f_ = rn(Tn, Hd).bfloat16(), rn(Tn, Hd).bfloat16()
-        W_ = (rn(Hd, 2 * Hd) / (2 * Hd) ** 0.5).bfloat16()
-        b_ = rn(Hd).bfloat16()
-        o_ = torch.empty(Tn, Hd, dtype=torch.bfloat16, device="cuda")
+        e_, f_ = rn(Tn, Hd).to(dt_), rn(Tn, Hd).to(dt_)
+        W_ = (rn(Hd, 2 * Hd) / (2 * Hd) ** 0.5).to(dt_)
+        b_ = rn(Hd).to(dt_)
+        o_ = torch.empty(Tn, Hd, dtype=dt_, device="cuda")
         t_dl, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: B.s4c_draft_linear(e_, f_, W_, o_, b_)))
         t_lib, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: torch.addmm(b_, torch.cat([e_, f_], 1), W_.t())))
         fl = 2.0 * Tn * 2 * Hd * Hd

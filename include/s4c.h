@@ -21,7 +21,8 @@
  *     and the affected sequence gets a defined result, never undefined behaviour.
  *   - Inputs are not modified except k_cache / v_cache / cache_len in s4c_kv_compact.
  *   - Row-major layouts, innermost dimension last.  dtype selects the element type of
- *     Q/K/V/cache/out (and of logits): fp32, or bf16 with fp32 accumulation.
+ *     Q/K/V/cache/out (and of logits): fp32, or bf16 / fp16 (IEEE binary16, the precision of the
+ *     paper's experiments, Sec. 4.1) with fp32 accumulation.
  *   - Limits: 1 <= N <= 128, D in {64, 128}, Hq % Hkv == 0.
  */
 #ifndef S4C_H
@@ -41,7 +42,7 @@ typedef enum {
     S4C_ERR_HIP = -5           /* kernel launch failed (hipGetLastError) */
 } s4c_status;
 
-typedef enum { S4C_F32 = 0, S4C_BF16 = 1 } s4c_dtype;
+typedef enum { S4C_F32 = 0, S4C_BF16 = 1, S4C_F16 = 2 } s4c_dtype;
 typedef enum { S4C_GREEDY = 0, S4C_STOCHASTIC = 1 } s4c_accept_mode;
 
 /* bits of the per-sequence device status word */
@@ -229,7 +230,7 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
  *   out[t][o] = bias[o] + sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k]
  *   e, f [T][H]: embedding and feature of every token; W [Hout][2H] (one row per output feature,
  *   the layout of a linear layer's weight); bias [Hout] nullable; out [T][Hout].
- *   dtype must be S4C_BF16 (products and sums in fp32, output rounded to nearest even);
+ *   dtype S4C_BF16 or S4C_F16 (products and sums in fp32, output rounded to nearest even);
  *   H a multiple of 32 (<= 16384), Hout a multiple of 256, T*H < 2^30; all pointers 16-byte
  *   aligned device pointers.  No workspace. */
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,

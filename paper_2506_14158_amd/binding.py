@@ -14,7 +14,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libs4c.so")
 
-S4C_F32, S4C_BF16 = 0, 1
+S4C_F32, S4C_BF16, S4C_F16 = 0, 1, 2
 S4C_GREEDY, S4C_STOCHASTIC = 0, 1
 S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 
@@ -115,7 +115,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return S4C_F32
     if t.dtype == torch.bfloat16:
         return S4C_BF16
-    raise TypeError("libs4c supports float32 and bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return S4C_F16
+    raise TypeError("libs4c supports float32, bfloat16 and float16, got %s" % t.dtype)
 
 
 def _stream() -> int:
@@ -317,7 +319,7 @@ def s4c_build_tree(draft_logits, nchild, root_token, kmax: int, parent, tokens, 
 
 
 def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
-    """out[t] = W @ concat(e[t], f[t]) + bias (bf16, fp32 accumulate); returns ``out``."""
+    """out[t] = W @ concat(e[t], f[t]) + bias (bf16 or fp16, fp32 accumulate); returns ``out``."""
     T, H = e.shape
     Hout = W.shape[0]
     if tuple(f.shape) != (T, H) or tuple(W.shape) != (Hout, 2 * H) or tuple(out.shape) != (T, Hout):
@@ -325,9 +327,9 @@ def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
     if bias is not None and tuple(bias.shape) != (Hout,):
         raise ValueError("bias [Hout]")
     for t in (e, f, W, out) + ((bias,) if bias is not None else ()):
-        if t.dtype != torch.bfloat16:
-            raise TypeError("s4c_draft_linear takes bfloat16 tensors")
-    _check(lib().s4c_draft_linear(T, H, Hout, S4C_BF16, _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out), _stream()))
+        if t.dtype != e.dtype or e.dtype not in (torch.bfloat16, torch.float16):
+            raise TypeError("s4c_draft_linear takes bfloat16 or float16 tensors of one type")
+    _check(lib().s4c_draft_linear(T, H, Hout, _dtype_code(e), _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out), _stream()))
     return out
 
 

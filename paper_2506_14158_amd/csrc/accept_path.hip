@@ -59,10 +59,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
                 } else {
                     const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        x[j * VN + 2 * k] = __uint_as_float(w[k] << 16);
-                        x[j * VN + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-                    }
+                    for (int k = 0; k < 4; ++k) unpack2<T>(w[k], x[j * VN + 2 * k], x[j * VN + 2 * k + 1]);
                 }
             }
         } else {
@@ -212,10 +209,12 @@ int accept_chunk_elems() { return kChunk; }
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
     dim3 grid((unsigned)(a.nseg * a.B * a.N)), block(kThreads);
     if (a.dtype == S4C_F32) hipLaunchKernelGGL(row_stats_kernel<float>, grid, block, 0, st, a);
+    else if (a.dtype == S4C_F16) hipLaunchKernelGGL(row_stats_kernel<f16_t>, grid, block, 0, st, a);
     else hipLaunchKernelGGL(row_stats_kernel<bf16_t>, grid, block, 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.dtype == S4C_F32) hipLaunchKernelGGL(path_kernel<float>, dim3(a.B), dim3(kMaxNodes), 0, st, a);
+    else if (a.dtype == S4C_F16) hipLaunchKernelGGL(path_kernel<f16_t>, dim3(a.B), dim3(kMaxNodes), 0, st, a);
     else hipLaunchKernelGGL(path_kernel<bf16_t>, dim3(a.B), dim3(kMaxNodes), 0, st, a);
     return hipGetLastError();
 }

@@ -22,7 +22,7 @@
 //
 // Vocabulary traversal (all passes): blocks of 512 tokens; workgroup g owns blocks
 // [g*bpg, (g+1)*bpg), wave w of it the blocks [w*ipw, (w+1)*ipw) of those; in a block lane l owns
-// the 8 tokens 8l..8l+7 (one 16-byte load of bf16 logits, two of fp32).
+// the 8 tokens 8l..8l+7 (one 16-byte load of 16-bit logits, two of fp32).
 #include "common.h"
 
 namespace s4c {
@@ -73,10 +73,7 @@ __device__ __forceinline__ void load_logits8(const Row& r, int base, float (&x)[
             const uint4 raw = *(const uint4*)(p + base);
             const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                x[2 * k] = __uint_as_float(w[k] << 16);
-                x[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-            }
+            for (int k = 0; k < 4; ++k) unpack2<T>(w[k], x[2 * k], x[2 * k + 1]);
         } else {
             const float4 a = *(const float4*)(p + base), b = *(const float4*)(p + base + 4);
             x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
@@ -430,6 +427,7 @@ hipError_t launch_accept_resample(const ResampleArgs& a, hipStream_t st) {
     }
     const dim3 grid((unsigned)(a.B * a.team));
     if (a.dtype == S4C_F32) hipLaunchKernelGGL(accept_resample_kernel<float>, grid, dim3(kThreads), 0, st, a);
+    else if (a.dtype == S4C_F16) hipLaunchKernelGGL(accept_resample_kernel<f16_t>, grid, dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL(accept_resample_kernel<bf16_t>, grid, dim3(kThreads), 0, st, a);
     return hipGetLastError();
 }

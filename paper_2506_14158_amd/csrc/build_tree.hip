@@ -177,6 +177,7 @@ int build_tree_chunk_elems() { return kChunk; }
 hipError_t launch_build_tree(const BuildArgs& a, hipStream_t st) {
     const dim3 grid1((unsigned)((size_t)a.B * a.N * a.chunks));
     if (a.dtype == S4C_F32) hipLaunchKernelGGL(topk_chunk_kernel<float>, grid1, dim3(kThreads), 0, st, a);
+    else if (a.dtype == S4C_F16) hipLaunchKernelGGL(topk_chunk_kernel<f16_t>, grid1, dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL(topk_chunk_kernel<bf16_t>, grid1, dim3(kThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -11,6 +11,7 @@ constexpr int kMaxNodes = 128;
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef uint16_t bf16_t;   // raw bf16 bits
+typedef _Float16 f16_t;    // IEEE binary16
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 
@@ -24,10 +25,25 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 template <typename T> __device__ __forceinline__ float to_f32(T x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t x) { return bf16_to_f32(x); }
+template <> __device__ __forceinline__ float to_f32<f16_t>(f16_t x) { return (float)x; }
 
 template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float x) { return (f16_t)x; }   // round to nearest even
+
+// the two 16-bit elements of a 32-bit word (low half first), as floats
+template <typename T> __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi);
+template <> __device__ __forceinline__ void unpack2<bf16_t>(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void unpack2<f16_t>(uint32_t w, float& lo, float& hi) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const h2 v = __builtin_bit_cast(h2, w);
+    lo = (float)v[0];
+    hi = (float)v[1];
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -59,8 +75,8 @@ struct AttnArgs {
 
 // launchers (defined in the kernel translation units); return hipGetLastError()
 hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st);
-hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st);
-hipError_t launch_tree_attn_smallm(const AttnArgs& a, hipStream_t st);   // M <= 64, called by the above
+hipError_t launch_tree_attn_mfma(const AttnArgs& a, int dtype, hipStream_t st);      // dtype: S4C_BF16 or S4C_F16
+hipError_t launch_tree_attn_smallm(const AttnArgs& a, int dtype, hipStream_t st);   // M <= 64, called by the above
 hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st);
 bool mfma_path_supported(const s4c_attn_shape& s);
 int mfma_rows_per_block(const s4c_attn_shape& s);
@@ -169,12 +185,12 @@ struct CommitArgs {
 hipError_t launch_commit(const CommitArgs& a, hipStream_t st);
 
 struct LinearArgs {
-    const void* e;       // [T][H] bf16
-    const void* f;       // [T][H] bf16
-    const void* W;       // [Hout][2H] bf16
-    const void* bias;    // [Hout] bf16 or null
-    void* out;           // [T][Hout] bf16
-    int32_t T, H, Hout;
+    const void* e;       // [T][H] bf16 or fp16
+    const void* f;       // [T][H]
+    const void* W;       // [Hout][2H]
+    const void* bias;    // [Hout] or null
+    void* out;           // [T][Hout]
+    int32_t T, H, Hout, dtype;
     int32_t ttiles, otiles;   // set by the launcher
 };
 hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st);

@@ -1,6 +1,6 @@
 // Input projection of a draft head (paper Eq. 3: h = Linear(concat[e, f])) on the CDNA4 matrix
 // cores: out[t][o] = bias[o] + sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k], bf16 in and
-// out, fp32 accumulate.  The concatenation is never materialised: the K loop walks the first H
+// out (fp16 likewise), fp32 accumulate.  The concatenation is never materialised: the K loop walks the first H
 // columns of W against e and the last H against f.
 //
 //   * Both operands have the reduction index contiguous in memory (W is [Hout][2H], e and f are
@@ -40,6 +40,7 @@ constexpr int kWaves = 8;
 constexpr int kTB = 2;                     // token blocks (of 32) per wave
 constexpr int kCH = 16 / kWaves;           // direct-to-LDS loads per wave and half-stage
 
+template <bool F16>
 __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void draft_linear_kernel(LinearArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -116,7 +117,7 @@ void draft_linear_kernel(LinearArgs a) {
         for (int ob = 0; ob < 8; ++ob)
 #pragma unroll
             for (int tb = 0; tb < 2 * kTB; ++tb)
-                acc[ob][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ob], xf[tb], acc[ob][tb], 0, 0, 0);
+                acc[ob][tb] = mma16<F16>(wf[ob], xf[tb], acc[ob][tb]);
     };
     issue(0);
     issue(1);                                              // nk is even (nk = 2 H / 32)
@@ -129,25 +130,26 @@ void draft_linear_kernel(LinearArgs a) {
     }
 
     // ---- epilogue: per block a lane holds features 4 (lane / 16) .. + 3 of token lane % 16
-    const bf16_t* bias = (const bf16_t*)a.bias;
+    const uint16_t* bias = (const uint16_t*)a.bias;
+    auto elem = [](uint16_t bits) { return F16 ? (float)__builtin_bit_cast(_Float16, bits) : bf16_to_f32(bits); };
 #pragma unroll
     for (int tb = 0; tb < 2 * kTB; ++tb) {
         const int tok = t0 + wt * (32 * kTB) + tb * 16 + l16;
         if (tok >= T) continue;
-        bf16_t* orow = (bf16_t*)a.out + (size_t)tok * a.Hout + o0 + wo * 128 + 4 * g16;
+        uint16_t* orow = (uint16_t*)a.out + (size_t)tok * a.Hout + o0 + wo * 128 + 4 * g16;
 #pragma unroll
         for (int ob = 0; ob < 8; ++ob) {
             float v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[u] = acc[ob][tb][u];
             if (bias) {
-                const bf16_t* bp = bias + o0 + wo * 128 + ob * 16 + 4 * g16;
+                const uint16_t* bp = bias + o0 + wo * 128 + ob * 16 + 4 * g16;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) v[u] += bf16_to_f32(bp[u]);
+                for (int u = 0; u < 4; ++u) v[u] += elem(bp[u]);
             }
             uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-            pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+            pk.x = round1<F16>(v[0]) | (round1<F16>(v[1]) << 16);
+            pk.y = round1<F16>(v[2]) | (round1<F16>(v[3]) << 16);
             *(uint2*)(orow + ob * 16) = pk;
         }
     }
@@ -158,17 +160,22 @@ void draft_linear_kernel(LinearArgs a) {
 int draft_linear_tile_out() { return kBO; }
 int draft_linear_tile_k() { return kBK; }
 
-hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st) {
+template <bool F16>
+static hipError_t launch_linear(const LinearArgs& a, hipStream_t st) {
     constexpr int kLds = kNS * kStage;
     static std::atomic<uint64_t> lds_set{0};
-    const hipError_t ea = ensure_dynamic_lds((const void*)draft_linear_kernel, kLds, lds_set);
+    const hipError_t ea = ensure_dynamic_lds((const void*)draft_linear_kernel<F16>, kLds, lds_set);
     if (ea != hipSuccess) return ea;
     LinearArgs k = a;
     k.ttiles = (a.T + kBT - 1) / kBT;
     k.otiles = a.Hout / kBO;
     const long units8 = ((long)k.otiles + 7) / 8 * 8;      // padded to whole XCD rounds
-    hipLaunchKernelGGL(draft_linear_kernel, dim3((unsigned)(units8 * k.ttiles)), dim3(kWaves * 64), kLds, st, k);
+    hipLaunchKernelGGL(draft_linear_kernel<F16>, dim3((unsigned)(units8 * k.ttiles)), dim3(kWaves * 64), kLds, st, k);
     return hipGetLastError();
+}
+
+hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st) {
+    return a.dtype == S4C_F16 ? launch_linear<true>(a, st) : launch_linear<false>(a, st);
 }
 
 }  // namespace s4c

@@ -9,7 +9,8 @@
 namespace s4c {
 namespace mfma {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));   // also the carrier of 8 fp16 elements (16 bytes)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -59,6 +60,43 @@ __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ float max_across_halves(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Element-type switch of the matrix-core kernels (F16: IEEE binary16, else bf16).  Fragments are
+// 16-byte vectors either way; only the multiply instruction and the two conversions differ.
+template <bool F16>
+__device__ __forceinline__ f32x16 mma32(const bf16x8& a, const bf16x8& b, const f32x16& c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <bool F16>
+__device__ __forceinline__ f32x4 mma16(const bf16x8& a, const bf16x8& b, const f32x4& c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// elements o .. o+7 of an accumulator block, rounded to nearest even
+template <bool F16>
+__device__ __forceinline__ bf16x8 round8(const f32x16& s, int o) {
+    if constexpr (F16) {
+        f16x8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = (_Float16)s[o + e];
+        return __builtin_bit_cast(bf16x8, r);
+    } else {
+        bf16x8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = (__bf16)s[o + e];
+        return r;
+    }
+}
+template <bool F16>
+__device__ __forceinline__ uint32_t round1(float x) {
+    if constexpr (F16) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x);
+    else return (uint32_t)f32_to_bf16(x);
 }
 
 }  // namespace mfma

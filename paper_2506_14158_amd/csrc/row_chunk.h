@@ -42,6 +42,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 template <typename T> struct Vec16;   // 16-byte vector of T
 template <> struct Vec16<float> { static constexpr int n = 4; };
 template <> struct Vec16<bf16_t> { static constexpr int n = 8; };
+template <> struct Vec16<f16_t> { static constexpr int n = 8; };
 
 // Thread tid's 32 logits of the chunk [c0, cend) of the row at `base`, as floats: vector j of
 // the thread holds the Vec16<T>::n consecutive tokens starting at idx0[j] (ascending in j and
@@ -67,10 +68,7 @@ __device__ __forceinline__ void load_chunk(const T* base, int c0, int cend, int 
                 } else {
                     const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        x[j * VN + 2 * k] = __uint_as_float(w[k] << 16);
-                        x[j * VN + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-                    }
+                    for (int k = 0; k < 4; ++k) unpack2<T>(w[k], x[j * VN + 2 * k], x[j * VN + 2 * k + 1]);
                 }
             } else {
 #pragma unroll

@@ -7,13 +7,15 @@ using namespace s4c;
 
 namespace {
 
+bool dtype_ok(int32_t d) { return d == S4C_F32 || d == S4C_BF16 || d == S4C_F16; }
+
 bool shape_ok(const s4c_attn_shape* s, s4c_status* why) {
     if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->D <= 0 || s->N <= 0 || s->S_cap < 0 ||
         s->Hq % s->Hkv != 0) {
         *why = S4C_ERR_SHAPE;
         return false;
     }
-    if (s->N > kMaxNodes || (s->D != 64 && s->D != 128) || (s->dtype != S4C_F32 && s->dtype != S4C_BF16) ||
+    if (s->N > kMaxNodes || (s->D != 64 && s->D != 128) || !dtype_ok(s->dtype) ||
         s->B > 65535 || s->Hkv > 65535) {
         *why = S4C_ERR_UNSUPPORTED;
         return false;
@@ -137,7 +139,7 @@ s4c_status tree_attn_impl(const s4c_attn_shape* shape, const void* q, const void
     hipStream_t st = (hipStream_t)hip_stream;
     // Splits are combined by a second kernel: the kernel boundary is what makes one workgroup's
     // partial results visible to another across the chip's separate L2s at no extra cost.
-    hipError_t e = p.mfma ? launch_tree_attn_mfma(a, st) : launch_tree_attn_generic(a, shape->dtype, st);
+    hipError_t e = p.mfma ? launch_tree_attn_mfma(a, shape->dtype, st) : launch_tree_attn_generic(a, shape->dtype, st);
     if (e == hipSuccess && p.splits > 1) e = launch_attn_merge(a, shape->dtype, st);
     return e == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
@@ -182,7 +184,7 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     if (!logits || !parent || !tokens || !path || !accept_len || !accepted_tokens || !bonus_token)
         return S4C_ERR_NULL;
     if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0) return S4C_ERR_SHAPE;
-    if (N > kMaxNodes || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16) ||
+    if (N > kMaxNodes || !dtype_ok(logits_dtype) ||
         (mode != S4C_GREEDY && mode != S4C_STOCHASTIC))
         return S4C_ERR_UNSUPPORTED;
     if (mode == S4C_STOCHASTIC) {
@@ -232,7 +234,7 @@ s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_d
         !accepted_tokens || !bonus_token)
         return S4C_ERR_NULL;
     if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0 || !(temperature > 0.f)) return S4C_ERR_SHAPE;
-    if (N > kMaxNodes || V > resample_max_vocab() || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16))
+    if (N > kMaxNodes || V > resample_max_vocab() || !dtype_ok(logits_dtype))
         return S4C_ERR_UNSUPPORTED;
     const size_t need = s4c_accept_resample_workspace_size(B, N, V, max_path);
     if (need > 0 && (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255))) return S4C_ERR_WORKSPACE;
@@ -323,7 +325,7 @@ s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
                           int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!draft_logits || !nchild || !root_token || !parent || !tokens || !p_draft) return S4C_ERR_NULL;
     if (B <= 0 || N <= 0 || V <= 0 || kmax <= 0 || !(temperature > 0.f)) return S4C_ERR_SHAPE;
-    if (N > kMaxNodes || kmax > build_tree_max_children() || (logits_dtype != S4C_F32 && logits_dtype != S4C_BF16))
+    if (N > kMaxNodes || kmax > build_tree_max_children() || !dtype_ok(logits_dtype))
         return S4C_ERR_UNSUPPORTED;
     const BuildLayout l = build_layout(B, N, V);
     if ((size_t)B * N * l.chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
@@ -374,12 +376,12 @@ s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, c
                             const void* W, const void* bias, void* out, void* hip_stream) {
     if (!e || !f || !W || !out) return S4C_ERR_NULL;
     if (T <= 0 || H <= 0 || Hout <= 0) return S4C_ERR_SHAPE;
-    if (dtype != S4C_BF16 || H % draft_linear_tile_k() != 0 || Hout % draft_linear_tile_out() != 0 ||
+    if ((dtype != S4C_BF16 && dtype != S4C_F16) || H % draft_linear_tile_k() != 0 || Hout % draft_linear_tile_out() != 0 ||
         (long long)T * H * 2 >= (1ll << 31) || H > 16384)
         return S4C_ERR_UNSUPPORTED;
     if ((((uintptr_t)e) | ((uintptr_t)f) | ((uintptr_t)W) | ((uintptr_t)out)) & 15) return S4C_ERR_SHAPE;
     LinearArgs a;
-    a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.T = T; a.H = H; a.Hout = Hout; a.ttiles = a.otiles = 0;
+    a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.T = T; a.H = H; a.Hout = Hout; a.dtype = dtype; a.ttiles = a.otiles = 0;
     return launch_draft_linear(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 

@@ -1,6 +1,6 @@
 // Tree-masked attention, scalar-FMA version (paper Sec. 3.2, Fig. 3).
 //
-// Used for fp32 data and for bf16 shapes the MFMA kernel does not take.  One workgroup owns
+// Used for fp32 data and for 16-bit shapes the MFMA kernels do not take.  One workgroup owns
 // a tile of kBM query rows of one (sequence, KV head) and one KV split: it streams key/value
 // tiles of kBN rows through LDS, keeps a running max / sum per row (online softmax in log2
 // units) and an fp32 output accumulator in registers.  The prefix rows come from the cache;
@@ -268,6 +268,9 @@ hipError_t launch_tree_attn_generic(const AttnArgs& a, int dtype, hipStream_t st
     if (dtype == S4C_F32) {
         if (a.D == 64) hipLaunchKernelGGL((tree_attn_generic_kernel<float, 64>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((tree_attn_generic_kernel<float, 128>), grid, block, 0, st, a);
+    } else if (dtype == S4C_F16) {
+        if (a.D == 64) hipLaunchKernelGGL((tree_attn_generic_kernel<f16_t, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((tree_attn_generic_kernel<f16_t, 128>), grid, block, 0, st, a);
     } else {
         if (a.D == 64) hipLaunchKernelGGL((tree_attn_generic_kernel<bf16_t, 64>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((tree_attn_generic_kernel<bf16_t, 128>), grid, block, 0, st, a);
@@ -281,6 +284,9 @@ hipError_t launch_attn_merge(const AttnArgs& a, int dtype, hipStream_t st) {
     if (dtype == S4C_F32) {
         if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<float, 64>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((attn_merge_kernel<float, 128>), grid, block, 0, st, a);
+    } else if (dtype == S4C_F16) {
+        if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<f16_t, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attn_merge_kernel<f16_t, 128>), grid, block, 0, st, a);
     } else {
         if (a.D == 64) hipLaunchKernelGGL((attn_merge_kernel<bf16_t, 64>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((attn_merge_kernel<bf16_t, 128>), grid, block, 0, st, a);

@@ -1,8 +1,8 @@
-// Tree-masked attention on the CDNA4 matrix cores (paper Sec. 3.2, Fig. 3): bf16 in, fp32
+// Tree-masked attention on the CDNA4 matrix cores (paper Sec. 3.2, Fig. 3): bf16 or fp16 in, fp32
 // accumulate, head size 128.
 //
 // The N tree nodes times the G query heads that share one KV head form a dense tile of
-// M = N*G query rows, so both contractions run on v_mfma_f32_32x32x16_bf16.
+// M = N*G query rows, so both contractions run on v_mfma_f32_32x32x16_bf16 (_f16 for fp16 data).
 //   * One workgroup = WR waves; wave w owns 32 query rows.  All waves share the K/V tiles
 //     (64 keys) that the workgroup streams from HBM straight into LDS with
 //     global_load_lds_dwordx4 (no staging registers), through a ring of NS tiles: the loads of
@@ -39,7 +39,7 @@ constexpr int kStageB = 2 * kTileB;         // K then V
 constexpr int lds_bytes_for(int ns) { return ns * kStageB + kMaxNodes * 16 + kMaxNodes * 4; }
 
 
-template <int WR, int NS, int WPE, bool PAGED>
+template <int WR, int NS, int WPE, bool PAGED, bool F16>
 __global__ __launch_bounds__(WR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void tree_attn_mfma_kernel(AttnArgs a) {
     constexpr int NT = WR * 64;
@@ -234,15 +234,15 @@ void tree_attn_mfma_kernel(AttnArgs a) {
             for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][tt], qf[tt], s[0], 0, 0, 0);
+                s[0] = mma32<F16>(kf[0][tt], qf[tt], s[0]);
                 kf[0][tt] = *(const lds_bf16x8*)(stage + k_off[tt + 4]);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][tt], qf[tt], s[1], 0, 0, 0);
+                s[1] = mma32<F16>(kf[1][tt], qf[tt], s[1]);
                 kf[1][tt] = *(const lds_bf16x8*)(stage + 32 * kRowB + k_off[tt + 4]);
             }
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][tt], qf[tt + 4], s[0], 0, 0, 0);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][tt], qf[tt + 4], s[1], 0, 0, 0);
+                s[0] = mma32<F16>(kf[0][tt], qf[tt + 4], s[0]);
+                s[1] = mma32<F16>(kf[1][tt], qf[tt + 4], s[1]);
             }
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // 8 LDS reads
 #pragma unroll
@@ -335,8 +335,7 @@ void tree_attn_mfma_kernel(AttnArgs a) {
             bf16x8 pb[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pb[st][e] = (__bf16)s[st >> 1][8 * (st & 1) + e];
+                pb[st] = round8<F16>(s[st >> 1], 8 * (st & 1));
             auto vfrag = [&](const lds_u8* p) {     // 8 keys x 1 column of V^T: two transposing reads
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * kRowB));
@@ -353,7 +352,7 @@ void tree_attn_mfma_kernel(AttnArgs a) {
                 }
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st & 1][db], pb[st], o[db], 0, 0, 0);
+                    o[db] = mma32<F16>(vf[st & 1][db], pb[st], o[db]);
             }
         }
     };
@@ -394,8 +393,8 @@ void tree_attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int jq = 0; jq < 4; ++jq) {
                 uint2 pk;
-                pk.x = (uint32_t)f32_to_bf16(o[db][4 * jq + 0] * inv) | ((uint32_t)f32_to_bf16(o[db][4 * jq + 1] * inv) << 16);
-                pk.y = (uint32_t)f32_to_bf16(o[db][4 * jq + 2] * inv) | ((uint32_t)f32_to_bf16(o[db][4 * jq + 3] * inv) << 16);
+                pk.x = round1<F16>(o[db][4 * jq + 0] * inv) | (round1<F16>(o[db][4 * jq + 1] * inv) << 16);
+                pk.y = round1<F16>(o[db][4 * jq + 2] * inv) | (round1<F16>(o[db][4 * jq + 3] * inv) << 16);
                 *(uint2*)(orow + 32 * db + 8 * jq) = pk;
             }
     } else {
@@ -418,23 +417,23 @@ void tree_attn_mfma_kernel(AttnArgs a) {
 
 int pick_wr(int M) { return M <= 128 ? 4 : 8; }
 
-template <int WR, int NS, int WPE, bool PAGED>
+template <int WR, int NS, int WPE, bool PAGED, bool F16>
 hipError_t launch(const AttnArgs& a, hipStream_t st) {
     constexpr int kLds = lds_bytes_for(NS);
     static std::atomic<uint64_t> lds_set{0};
-    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_mfma_kernel<WR, NS, WPE, PAGED>, kLds, lds_set);
+    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_mfma_kernel<WR, NS, WPE, PAGED, F16>, kLds, lds_set);
     if (ea != hipSuccess) return ea;
     AttnArgs k = a;
     k.mtiles = (a.M + WR * 32 - 1) / (WR * 32);
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;          // padded to whole XCD rounds
     dim3 grid((unsigned)(units8 * k.mtiles * a.splits)), block(WR * 64);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR, NS, WPE, PAGED>), grid, block, kLds, st, k);
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<WR, NS, WPE, PAGED, F16>), grid, block, kLds, st, k);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool mfma_path_supported(const s4c_attn_shape& s) { return s.dtype == S4C_BF16 && s.D == kD; }
+bool mfma_path_supported(const s4c_attn_shape& s) { return (s.dtype == S4C_BF16 || s.dtype == S4C_F16) && s.D == kD; }
 
 // Few rows: the key-parallel kernel (one 64-row workgroup); otherwise 32 rows per wave.
 int mfma_rows_per_block(const s4c_attn_shape& s) {
@@ -442,10 +441,15 @@ int mfma_rows_per_block(const s4c_attn_shape& s) {
     return M <= 64 ? 64 : 32 * pick_wr(M);
 }
 
-hipError_t launch_tree_attn_mfma(const AttnArgs& a, hipStream_t st) {
-    if (a.M <= 64) return launch_tree_attn_smallm(a, st);
-    if (a.block_table) return pick_wr(a.M) == 4 ? launch<4, 4, 1, true>(a, st) : launch<8, 4, 2, true>(a, st);
-    return pick_wr(a.M) == 4 ? launch<4, 4, 1, false>(a, st) : launch<8, 4, 2, false>(a, st);
+template <bool F16>
+static hipError_t launch_by_shape(const AttnArgs& a, hipStream_t st) {
+    if (a.block_table) return pick_wr(a.M) == 4 ? launch<4, 4, 1, true, F16>(a, st) : launch<8, 4, 2, true, F16>(a, st);
+    return pick_wr(a.M) == 4 ? launch<4, 4, 1, false, F16>(a, st) : launch<8, 4, 2, false, F16>(a, st);
+}
+
+hipError_t launch_tree_attn_mfma(const AttnArgs& a, int dtype, hipStream_t st) {
+    if (a.M <= 64) return launch_tree_attn_smallm(a, dtype, st);
+    return dtype == S4C_F16 ? launch_by_shape<true>(a, st) : launch_by_shape<false>(a, st);
 }
 
 }  // namespace s4c

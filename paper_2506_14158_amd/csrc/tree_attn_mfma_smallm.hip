@@ -39,7 +39,7 @@ struct Cfg {
     static constexpr int kLdsBytes = (kRingB + kAuxB > kMergeB) ? kRingB + kAuxB : kMergeB;
 };
 
-template <int kKG, bool PAGED>
+template <int kKG, bool PAGED, bool F16>
 __global__ __launch_bounds__(Cfg<kKG>::kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_smallm_kernel(AttnArgs a) {
     constexpr int kRoundB = Cfg<kKG>::kRoundB, kRingB = Cfg<kKG>::kRingB, kWaves = Cfg<kKG>::kWaves;
@@ -221,8 +221,8 @@ void tree_attn_smallm_kernel(AttnArgs a) {
             for (int j = 0; j < 16; ++j) { s[j] = 0.f; s1[j] = 0.f; }
 #pragma unroll
             for (int tt = 0; tt < 8; tt += 2) {        // two chains over the head dimension, summed below
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt], qf[tt], s, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[tt + 1], qf[tt + 1], s1, 0, 0, 0);
+                s = mma32<F16>(kf[tt], qf[tt], s);
+                s1 = mma32<F16>(kf[tt + 1], qf[tt + 1], s1);
             }
 #pragma unroll
             for (int j = 0; j < 16; ++j) s[j] += s1[j];
@@ -266,8 +266,7 @@ void tree_attn_smallm_kernel(AttnArgs a) {
         bf16x8 pb[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pb[st][e] = (__bf16)s[8 * st + e];
+            pb[st] = round8<F16>(s, 8 * st);
         auto vfrag = [&](const lds_u8* p) {
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * kRowB));
@@ -282,7 +281,7 @@ void tree_attn_smallm_kernel(AttnArgs a) {
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int db = 0; db < 4; ++db)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pb[st], o[db], 0, 0, 0);
+                o[db] = mma32<F16>(vf[st][db], pb[st], o[db]);
     };
 
     // ---- round pipeline: round r+1 is in flight while round r is consumed
@@ -365,7 +364,7 @@ void tree_attn_smallm_kernel(AttnArgs a) {
             uint32_t pk[4];
 #pragma unroll
             for (int h = 0; h < 4; ++h)
-                pk[h] = (uint32_t)f32_to_bf16(acc[e + 2 * h] * inv) | ((uint32_t)f32_to_bf16(acc[e + 2 * h + 1] * inv) << 16);
+                pk[h] = round1<F16>(acc[e + 2 * h] * inv) | (round1<F16>(acc[e + 2 * h + 1] * inv) << 16);
             dst[e / 8] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     } else {
@@ -384,19 +383,20 @@ void tree_attn_smallm_kernel(AttnArgs a) {
 
 }  // namespace
 
-template <int KG, bool PAGED>
+template <int KG, bool PAGED, bool F16>
 static hipError_t launch_smallm(const AttnArgs& a, hipStream_t st) {
     static std::atomic<uint64_t> lds_set{0};
-    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_smallm_kernel<KG, PAGED>, Cfg<KG>::kLdsBytes, lds_set);
+    const hipError_t ea = ensure_dynamic_lds((const void*)tree_attn_smallm_kernel<KG, PAGED, F16>, Cfg<KG>::kLdsBytes, lds_set);
     if (ea != hipSuccess) return ea;
     const long units8 = ((long)a.B * a.Hkv + 7) / 8 * 8;
     dim3 grid((unsigned)(units8 * a.splits)), block(Cfg<KG>::kThreads);
-    hipLaunchKernelGGL((tree_attn_smallm_kernel<KG, PAGED>), grid, block, Cfg<KG>::kLdsBytes, st, a);
+    hipLaunchKernelGGL((tree_attn_smallm_kernel<KG, PAGED, F16>), grid, block, Cfg<KG>::kLdsBytes, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_tree_attn_smallm(const AttnArgs& a, hipStream_t st) {
-    return a.block_table ? launch_smallm<2, true>(a, st) : launch_smallm<2, false>(a, st);
+hipError_t launch_tree_attn_smallm(const AttnArgs& a, int dtype, hipStream_t st) {
+    if (dtype == S4C_F16) return a.block_table ? launch_smallm<2, true, true>(a, st) : launch_smallm<2, false, true>(a, st);
+    return a.block_table ? launch_smallm<2, true, false>(a, st) : launch_smallm<2, false, false>(a, st);
 }
 
 }  // namespace s4c

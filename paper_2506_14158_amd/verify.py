@@ -16,7 +16,7 @@ class TreeVerifier:
                  device="cuda"):
         self.B, self.N, self.Hq, self.Hkv, self.D, self.S_cap, self.V = B, N, Hq, Hkv, D, S_cap, V
         self.dtype, self.max_path, self.max_cache_len = dtype, max_path, max_cache_len
-        code = _b.S4C_F32 if dtype == torch.float32 else _b.S4C_BF16
+        code = {torch.float32: _b.S4C_F32, torch.bfloat16: _b.S4C_BF16, torch.float16: _b.S4C_F16}[dtype]
         self.shape = _b.AttnShape(B, Hq, Hkv, D, N, S_cap, code)
         i32 = dict(dtype=torch.int32, device=device)
         self.out = torch.empty(B, N, Hq, D, dtype=dtype, device=device)

@@ -12,7 +12,7 @@ from tests.util import attn_errors, to_device
 
 pytestmark = pytest.mark.gpu
 C = synth.CONFIGS
-TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2)}
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2), "f16": (2.5e-3, 2.5e-3)}
 
 
 def scatter_to_pool(cache_np, page_size, rng, spare=5):
@@ -22,7 +22,7 @@ def scatter_to_pool(cache_np, page_size, rng, spare=5):
     num_pages = Bn * max_blocks + spare
     bt = rng.permutation(num_pages)[:Bn * max_blocks].reshape(Bn, max_blocks).astype(np.int32)
     pool = rng.integers(0, 2 ** 15, size=(num_pages, Hkv, page_size, D)).astype(cache_np.dtype) if cache_np.dtype == np.uint16 \
-        else rng.standard_normal((num_pages, Hkv, page_size, D)).astype(np.float32)
+        else rng.standard_normal((num_pages, Hkv, page_size, D)).astype(cache_np.dtype)
     pad = np.zeros((Bn, Hkv, max_blocks * page_size, D), dtype=cache_np.dtype)
     pad[:, :, :S] = cache_np
     for b in range(Bn):

@@ -16,13 +16,13 @@ from tests.util import accept_inputs_with_margin, attn_errors, to_device
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2)}
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 2e-2), "f16": (2.5e-3, 2.5e-3)}
 C = synth.CONFIGS
 
 
 def verifier(cfg, d, max_cache_len=None):
     return TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, cfg.S_cap, cfg.V, d["q"].dtype if "q" in d else
-                        (torch.float32 if cfg.dtype == "f32" else torch.bfloat16), cfg.levels,
+                        {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[cfg.dtype], cfg.levels,
                         cfg.P if max_cache_len is None else max_cache_len)
 
 
