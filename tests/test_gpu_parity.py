@@ -12,6 +12,7 @@ import torch
 from oracle import s4c_oracle as O
 from paper_2506_14158_amd import binding as B, synth
 from paper_2506_14158_amd.verify import TreeVerifier
+from paper_2506_14158_amd.device import np_to_torch as np_to_dev
 from tests.util import accept_inputs_with_margin, attn_errors, to_device
 
 pytestmark = pytest.mark.gpu
@@ -366,3 +367,45 @@ def test_step_replays_from_a_hip_graph():
         for a_, b_ in zip(got, ref):
             assert torch.equal(a_.view(torch.uint8) if a_.dtype == torch.bfloat16 else a_,
                                b_.view(torch.uint8) if b_.dtype == torch.bfloat16 else b_), rep
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_consecutive_steps_share_one_growing_cache(dtype):
+    """The continuous use of the step (Sec. 3.2: accepted tokens' features are kept for the following
+    rounds): several rounds, each with a new tree, new Q and tree K/V and new logits, over ONE cache that
+    the compaction of the round before has extended.  Every round's attention output, path and cache
+    bytes must match the oracle run through the same rounds."""
+    base = C[4] if dtype == "bf16" else C[1]
+    cfg = synth.scaled(base, name="rounds-" + dtype, B=3, P=200, V=3000, ragged=True, mode="greedy", index=0,
+                       **({"Hq": 8, "Hkv": 2} if dtype == "bf16" else {}))
+    at = synth.make_attn_inputs(cfg)
+    kc, vc, cl = at.k_cache.copy(), at.v_cache.copy(), at.cache_len.copy()       # the oracle's cache
+    d_kc, d_vc = np_to_dev(kc), np_to_dev(vc)
+    d_cl = torch.from_numpy(cl.copy()).cuda()
+    tv = None
+    grown = 0
+    rounds = 4 if dtype == "bf16" else 3          # rows appended stay within S_cap = P + N
+    for rnd in range(rounds):
+        seed = cfg.seed() + 77 * (rnd + 1)
+        par = synth.make_parent(cfg, seed=seed)
+        a = synth.make_attn_inputs(cfg, seed=seed)                                # only q / k_tree / v_tree are used
+        ac = synth.make_accept_inputs(cfg, par, seed=seed)
+        d = to_device(cfg, par, None, ac)
+        q, kt, vt = np_to_dev(a.q), np_to_dev(a.k_tree), np_to_dev(a.v_tree)
+        if tv is None:
+            tv = TreeVerifier(cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.D, cfg.S_cap, cfg.V, q.dtype, cfg.levels, cfg.S_cap)
+        tv.step(q, kt, vt, d_kc, d_vc, d_cl, d["parent"], d["logits"], d["tokens"], B.S4C_GREEDY)
+        torch.cuda.synchronize()
+        ref, st = O.tree_attn(a.q, a.k_tree, a.v_tree, kc, vc, cl, par)           # on the cache BEFORE this round's append
+        assert (st == 0).all() and tv.attn_status.cpu().tolist() == [0] * cfg.B
+        amax, rel = attn_errors(tv.out, ref)
+        assert amax <= TOL[dtype][0] and rel <= TOL[dtype][1], (rnd, amax, rel)
+        r = O.accept_path(ac.logits, par, ac.tokens, "greedy", cfg.levels)
+        assert np.array_equal(tv.path.cpu().numpy(), r["path"]), rnd
+        dst, st2 = O.kv_compact(a.k_tree, a.v_tree, kc, vc, cl, r["path"], r["accept_len"])
+        assert (st2 == 0).all() and tv.compact_status.cpu().tolist() == [0] * cfg.B
+        assert np.array_equal(d_cl.cpu().numpy(), cl), rnd
+        bits = lambda t: t.cpu().contiguous().view(torch.uint8).numpy()
+        assert np.array_equal(bits(d_kc), kc.view(np.uint8)) and np.array_equal(bits(d_vc), vc.view(np.uint8)), rnd
+        grown += int(r["accept_len"].sum()) + cfg.B
+    assert int((cl - at.cache_len).sum()) == grown and grown >= rounds * cfg.B
