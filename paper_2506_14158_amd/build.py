@@ -44,5 +44,23 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "verify_step.c")
+C_CLIENT_BIN = os.path.join(ROOT, "tests", "c_client", "verify_step")
+
+
+def build_c_client() -> str:
+    """The plain-C test client of the C ABI (gcc, linked against libs4c.so and the HIP runtime)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c11", "-O1", "-Wall", "-I" + os.path.join(rocm, "include"),
+           "-I" + os.path.join(ROOT, "include"), C_CLIENT_SRC, "-o", C_CLIENT_BIN, "-L" + PKG, "-ls4c",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/../../paper_2506_14158_amd",
+           "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("C client build failed:\n" + r.stderr[-4000:])
+    return C_CLIENT_BIN
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_c_client())
