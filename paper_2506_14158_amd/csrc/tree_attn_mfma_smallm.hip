@@ -85,39 +85,6 @@ void tree_attn_smallm_kernel(AttnArgs a) {
     if (a.status && tid == 0 && sp == 0 && kvh == 0)
         a.status[b] = (bad_tree ? S4C_SEQ_BAD_TREE : 0) | (bad_len ? S4C_SEQ_BAD_LEN : 0);
     const bool bad = __builtin_amdgcn_readfirstlane((bad_tree || bad_len) ? 1 : 0) != 0;
-    for (int i = tid; i < N && !bad; i += kThreads) {
-        const int tid_ = i;
-        uint32_t m[4] = {0, 0, 0, 0};
-        for (int j = tid_; j >= 0; j = spar[j]) m[j >> 5] |= 1u << (j & 31);
-        anc[tid_ * 4 + 0] = m[0]; anc[tid_ * 4 + 1] = m[1]; anc[tid_ * 4 + 2] = m[2]; anc[tid_ * 4 + 3] = m[3];
-    }
-    __syncthreads();
-
-    // ---- this lane's query row
-    const int g32 = lane >> 5;
-    const int rq = rb * 32 + (lane & 31);
-    const bool rvalid = rq < M;
-    const int node = rvalid ? rq / G : 0;
-    const int head = kvh * G + (rvalid ? rq % G : 0);
-    // ancestor words of this row, pre-shifted for this half of the wave; tree round i of key group kg
-    // covers nodes 32 (i KG + kg) ..
-    uint32_t amask[4] = {0, 0, 0, 0};
-    if (rvalid && !bad) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) amask[w] = anc[node * 4 + w] >> (4 * g32);
-    }
-
-    bf16x8 qf[8];
-    {
-        const bf16_t* qrow = (const bf16_t*)a.q + (((size_t)b * N + node) * a.Hq + head) * kD + g32 * 8;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (rvalid) raw = *(const uint4*)(qrow + 16 * t);
-            qf[t] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
-
     // ---- rounds of this workgroup: prefix range of the split, then (last split) the tree round
     int kb = sp * a.chunk, ke = min(P, (sp + 1) * a.chunk);
     if (bad || ke < kb) { kb = 0; ke = 0; }
@@ -188,6 +155,45 @@ void tree_attn_smallm_kernel(AttnArgs a) {
             }
         }
     };
+
+    // Round 0 starts streaming now; the Q fragments are requested right behind it and the
+    // ancestor masks are built while both are in flight.  (The direct-to-LDS loads are invisible
+    // to the compiler; loads it does know about may follow them, since completion is in order and
+    // its waits then only become stricter.)
+    if (n_rounds > 0) issue_round(0);
+
+    // ---- this lane's query row
+    const int g32 = lane >> 5;
+    const int rq = rb * 32 + (lane & 31);
+    const bool rvalid = rq < M;
+    const int node = rvalid ? rq / G : 0;
+    const int head = kvh * G + (rvalid ? rq % G : 0);
+    bf16x8 qf[8];
+    {
+        const bf16_t* qrow = (const bf16_t*)a.q + (((size_t)b * N + node) * a.Hq + head) * kD + g32 * 8;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (rvalid) raw = *(const uint4*)(qrow + 16 * t);
+            qf[t] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    for (int i = tid; i < N && !bad; i += kThreads) {
+        const int tid_ = i;
+        uint32_t m[4] = {0, 0, 0, 0};
+        for (int j = tid_; j >= 0; j = spar[j]) m[j >> 5] |= 1u << (j & 31);
+        anc[tid_ * 4 + 0] = m[0]; anc[tid_ * 4 + 1] = m[1]; anc[tid_ * 4 + 2] = m[2]; anc[tid_ * 4 + 3] = m[3];
+    }
+    __syncthreads();
+
+    // ancestor words of this row, pre-shifted for this half of the wave; tree round i of key group kg
+    // covers nodes 32 (i KG + kg) ..
+    uint32_t amask[4] = {0, 0, 0, 0};
+    if (rvalid && !bad) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) amask[w] = anc[node * 4 + w] >> (4 * g32);
+    }
 
     // per-lane LDS byte offsets inside a tile
     const int i16 = lane & 15, dhalf = (lane >> 4) & 1;
@@ -285,8 +291,11 @@ void tree_attn_smallm_kernel(AttnArgs a) {
     };
 
     // ---- round pipeline: round r+1 is in flight while round r is consumed
-    wait_vmcnt<0>();               // settle the compiler-visible loads (Q) before the untracked ones start
-    if (n_rounds > 0) issue_round(0);
+    // Settle the compiler-visible loads (Q) here, so that it places no vmcnt wait of its own inside
+    // the round loop (which would also wait for the round just issued).
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(qf[t]));
     auto sync_and_prefetch = [&](int r) {
         wait_vmcnt<0>();           // this wave's share of round r has landed
         __syncthreads();           // everybody's has; round r-1's half of the ring is free
