@@ -596,3 +596,46 @@ int oracle_kv_compact_paged(const oracle_shape* s, int32_t page_size, int32_t nu
     return 0;
 }
 
+/* Whole-model commit into paged pools: k_pool, v_pool are [layers][num_pages][Hkv][page_size][D], one
+ * block table serves every layer (a sequence's row j sits at the same page slot in all of them). */
+int oracle_commit_path_paged(const oracle_shape* s, int32_t layers, int32_t page_size, int32_t num_pages,
+                             int32_t max_blocks, const void* k_tree, const void* v_tree, void* k_pool, void* v_pool,
+                             const int32_t* block_table, int32_t* cache_len, const int32_t* path,
+                             const int32_t* accept_len, int32_t max_path, const void* features, int32_t feature_bytes,
+                             void* features_out, int32_t* dst_index, int32_t* status) {
+    const size_t row = (size_t)s->D * elem_size(s->dtype);
+    const size_t tree_layer = (size_t)s->B * s->N * s->Hkv * row;
+    const size_t pool_layer = (size_t)num_pages * s->Hkv * page_size * row;
+    for (int32_t b = 0; b < s->B; ++b) {
+        const int32_t L = accept_len[b];
+        const int32_t base = cache_len[b];
+        const int32_t* pth = path + (size_t)b * max_path;
+        if (dst_index)
+            for (int32_t k = 0; k < max_path; ++k) dst_index[(size_t)b * max_path + k] = -1;
+        int bad = (L < 0 || L >= max_path || base < 0 || (int64_t)base + L + 1 > (int64_t)max_blocks * page_size);
+        for (int32_t k = 0; !bad && k <= L; ++k) {
+            if (pth[k] < 0 || pth[k] >= s->N) bad = 1;
+            const int32_t id = block_table[(size_t)b * max_blocks + (base + k) / page_size];
+            if (id < 0 || id >= num_pages) bad = 1;
+        }
+        if (status) status[b] = bad ? ORACLE_BAD_LEN : 0;
+        if (bad) continue;
+        for (int32_t k = 0; k <= L; ++k) {
+            const int32_t j = base + k;
+            const int32_t id = block_table[(size_t)b * max_blocks + j / page_size];
+            for (int32_t l = 0; l < layers; ++l)
+                for (int32_t h = 0; h < s->Hkv; ++h) {
+                    const size_t src = l * tree_layer + (((size_t)b * s->N + pth[k]) * s->Hkv + h) * row;
+                    const size_t dst = l * pool_layer + (((size_t)id * s->Hkv + h) * page_size + (size_t)(j % page_size)) * row;
+                    memcpy((char*)k_pool + dst, (const char*)k_tree + src, row);
+                    memcpy((char*)v_pool + dst, (const char*)v_tree + src, row);
+                }
+            if (features && features_out)
+                memcpy((char*)features_out + ((size_t)b * max_path + k) * feature_bytes,
+                       (const char*)features + ((size_t)b * s->N + pth[k]) * feature_bytes, (size_t)feature_bytes);
+            if (dst_index) dst_index[(size_t)b * max_path + k] = j;
+        }
+        cache_len[b] = base + L + 1;
+    }
+    return 0;
+}

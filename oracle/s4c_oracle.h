@@ -157,6 +157,14 @@ int oracle_kv_compact_paged(const oracle_shape* s, int32_t page_size, int32_t nu
                             const int32_t* block_table, int32_t* cache_len, const int32_t* path,
                             const int32_t* accept_len, int32_t max_path, int32_t* dst_index, int32_t* status);
 
+/* oracle_commit_path into paged pools [layers][num_pages][Hkv][page_size][D]; one block table serves every
+ * layer.  Flagging as in oracle_kv_compact_paged; a flagged sequence is untouched everywhere. */
+int oracle_commit_path_paged(const oracle_shape* s, int32_t layers, int32_t page_size, int32_t num_pages,
+                             int32_t max_blocks, const void* k_tree, const void* v_tree, void* k_pool, void* v_pool,
+                             const int32_t* block_table, int32_t* cache_len, const int32_t* path,
+                             const int32_t* accept_len, int32_t max_path, const void* features, int32_t feature_bytes,
+                             void* features_out, int32_t* dst_index, int32_t* status);
+
 /* Input projection of a draft head (Eq. 3: h = Linear(concat[e, f])): out[t][o] = bias[o] +
  * sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k], in double.  e, f [T][H]; W [Hout][2H] (one row
  * per output feature, the layout of a linear layer's weight); bias [Hout] nullable; out [T][Hout]. */

@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
-                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged", "oracle_decode"):
+                     "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged", "oracle_decode", "oracle_commit_path_paged"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -276,5 +276,34 @@ def kv_compact_paged(k_tree, v_tree, k_pool, v_pool, block_table, cache_len, pat
     rc = lib.oracle_kv_compact_paged(C.byref(s), C.c_int32(page_size), C.c_int32(num_pages), C.c_int32(max_blocks),
                                      _p(k_tree), _p(v_tree), _p(k_pool), _p(v_pool), _p(block_table), _p(cache_len),
                                      _p(path), _p(accept_len), C.c_int32(max_path), _p(dst), _p(status))
+    assert rc == 0
+    return dst, status
+
+
+def commit_path_paged(k_tree, v_tree, k_pool, v_pool, block_table, cache_len, path, accept_len, features=None,
+                      features_out=None):
+    """Multi-layer compaction into paged pools [layers][num_pages][Hkv][page][D] (one block table for all
+    layers), in place on the pools, cache_len and features_out -> (dst_index, status)"""
+    lib = _load()
+    Ly, B, N, Hkv, D = k_tree.shape
+    _, num_pages, _, page_size, _ = k_pool.shape
+    assert k_pool.shape == (Ly, num_pages, Hkv, page_size, D) and v_pool.shape == k_pool.shape and v_tree.shape == k_tree.shape
+    block_table = _i32(block_table)
+    max_blocks = block_table.shape[1]
+    s = _Shape(B, Hkv, Hkv, D, N, max_blocks * page_size, _dt(k_tree))
+    assert cache_len.dtype == np.int32 and cache_len.flags["C_CONTIGUOUS"]
+    path, accept_len = _i32(path), _i32(accept_len)
+    max_path = path.shape[1]
+    fb = 0
+    if features is not None:
+        assert features.shape[:2] == (B, N) and features_out.shape[:2] == (B, max_path)
+        fb = int(features[0, 0].nbytes)
+        assert int(features_out[0, 0].nbytes) == fb
+    dst = np.empty((B, max_path), dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib.oracle_commit_path_paged(C.byref(s), C.c_int32(Ly), C.c_int32(page_size), C.c_int32(num_pages),
+                                      C.c_int32(max_blocks), _p(k_tree), _p(v_tree), _p(k_pool), _p(v_pool), _p(block_table),
+                                      _p(cache_len), _p(path), _p(accept_len), C.c_int32(max_path), _p(features),
+                                      C.c_int32(fb), _p(features_out), _p(dst), _p(status))
     assert rc == 0
     return dst, status

@@ -339,3 +339,60 @@ def test_paged_gather_and_paged_compaction_match_the_contiguous_layout():
     kp3, clq = kp.copy(), clp.copy()
     d3, s3 = O.kv_compact_paged(kt, vt, kp3, vp.copy(), bt_bad, clq, path, alen)
     assert s3.tolist() == [0, 2, 0] and clq[1] == clp[1]
+
+
+def test_paged_multi_layer_commit_matches_the_contiguous_one_and_plain_numpy():
+    """oracle_commit_path_paged against (1) oracle_commit_path on the equivalent contiguous caches,
+    seen through the block table layer by layer, and (2) a direct numpy scatter."""
+    rng = np.random.default_rng(31)
+    Ly, B, N, Hkv, D, S, ps, F = 3, 3, 9, 2, 8, 48, 16, 5
+    cl = np.array([20, 33, 0], dtype=np.int32)
+    kc = rng.standard_normal((Ly, B, Hkv, S, D)).astype(np.float32)
+    vc = rng.standard_normal((Ly, B, Hkv, S, D)).astype(np.float32)
+    for b in range(B):
+        kc[:, b, :, cl[b]:] = 0
+        vc[:, b, :, cl[b]:] = 0
+    max_blocks = S // ps
+    num_pages = B * max_blocks + 4
+    bt = rng.permutation(num_pages)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    kp = rng.standard_normal((Ly, num_pages, Hkv, ps, D)).astype(np.float32)
+    vp = rng.standard_normal((Ly, num_pages, Hkv, ps, D)).astype(np.float32)
+    for l in range(Ly):
+        for b in range(B):
+            for j in range(S):
+                kp[l, bt[b, j // ps], :, j % ps] = kc[l, b, :, j]
+                vp[l, bt[b, j // ps], :, j % ps] = vc[l, b, :, j]
+    kp0, vp0 = kp.copy(), vp.copy()
+    kt = rng.standard_normal((Ly, B, N, Hkv, D)).astype(np.float32)
+    vt = rng.standard_normal((Ly, B, N, Hkv, D)).astype(np.float32)
+    feats = rng.standard_normal((B, N, F)).astype(np.float32)
+    path = np.array([[0, 2, 5, -1], [0, -1, -1, -1], [0, 1, 3, 7]], dtype=np.int32)
+    alen = np.array([2, 0, 3], dtype=np.int32)
+    fo1 = np.full((B, 4, F), -7.0, dtype=np.float32)
+    fo2 = fo1.copy()
+    kc2, vc2, cl2 = kc.copy(), vc.copy(), cl.copy()
+    d1, s1 = O.commit_path(kt, vt, kc2, vc2, cl2, path, alen, feats, fo1)
+    clp = cl.copy()
+    d2, s2 = O.commit_path_paged(kt, vt, kp, vp, bt, clp, path, alen, feats, fo2)
+    assert np.array_equal(d1, d2) and np.array_equal(s1, s2) and np.array_equal(cl2, clp) and np.array_equal(fo1, fo2)
+    for l in range(Ly):
+        gk, st = O.paged_gather(kp[l], bt, clp, S)
+        gv, _ = O.paged_gather(vp[l], bt, clp, S)
+        assert (st == 0).all() and np.array_equal(gk, kc2[l]) and np.array_equal(gv, vc2[l])
+    # direct numpy scatter of the same rows; every other byte of the pools untouched
+    ke, ve = kp0.copy(), vp0.copy()
+    for b in range(B):
+        for k in range(alen[b] + 1):
+            j = cl[b] + k
+            ke[:, bt[b, j // ps], :, j % ps] = kt[:, b, path[b, k]]
+            ve[:, bt[b, j // ps], :, j % ps] = vt[:, b, path[b, k]]
+    assert np.array_equal(kp, ke) and np.array_equal(vp, ve)
+    # a bad page id flags the sequence and leaves it alone in every layer
+    bt_bad = bt.copy()
+    bt_bad[2, 0] = -1
+    kq, vq, clq = kp0.copy(), vp0.copy(), cl.copy()
+    d3, s3 = O.commit_path_paged(kt, vt, kq, vq, bt_bad, clq, path, alen)
+    assert s3.tolist() == [0, 0, 2] and clq.tolist() == [23, 34, 0] and (d3[2] == -1).all()
+    for l in range(Ly):
+        for pg in bt[2]:
+            assert np.array_equal(kq[l, pg], kp0[l, pg])
