@@ -226,6 +226,16 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
                            int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
                            void* hip_stream);
 
+/* s4c_commit_path into paged pools: k_pool, v_pool [layers][num_pages][Hkv][page_size][D], one block table
+ * [B][max_blocks] for every layer (layout and flagging as in s4c_kv_compact_paged; shape->S_cap is
+ * ignored).  Everything else as s4c_commit_path. */
+s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                                 void* k_pool, void* v_pool, const int32_t* block_table, int32_t max_blocks,
+                                 int32_t page_size, int32_t num_pages, int32_t* cache_len, const int32_t* path,
+                                 const int32_t* accept_len, int32_t max_path, const void* features,
+                                 int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
+                                 void* hip_stream);
+
 /* Input projection of a draft head (Eq. 3: h = Linear(concat[e, f])), the concatenation never formed:
  *   out[t][o] = bias[o] + sum_k e[t][k] W[o][k] + sum_k f[t][k] W[o][H + k]
  *   e, f [T][H]: embedding and feature of every token; W [Hout][2H] (one row per output feature,

@@ -21,7 +21,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
+           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
 
 
 class S4CError(RuntimeError):
@@ -68,6 +68,9 @@ def lib() -> C.CDLL:
         L.s4c_commit_path.restype = C.c_int
         L.s4c_commit_path.argtypes = [C.POINTER(AttnShape), C.c_int32] + [C.c_void_p] * 7 + [C.c_int32, C.c_void_p,
                                                                                           C.c_int32] + [C.c_void_p] * 4
+        L.s4c_commit_path_paged.restype = C.c_int
+        L.s4c_commit_path_paged.argtypes = [C.POINTER(AttnShape), C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 3 + \
+            [C.c_void_p] * 3 + [C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         L.s4c_build_tree_workspace_size.restype = C.c_size_t
         L.s4c_build_tree_workspace_size.argtypes = [C.c_int32] * 3
         L.s4c_build_tree.restype = C.c_int
@@ -295,6 +298,35 @@ def s4c_commit_path(k_tree, v_tree, k_cache, v_cache, cache_len, path, accept_le
     _check(lib().s4c_commit_path(C.byref(shape), int(Ly), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
                                  _ptr(cache_len), _ptr(path), _ptr(accept_len), max_path, _ptr(features), fb,
                                  _ptr(features_out), _ptr(dst_index), _ptr(status), _stream()))
+
+
+def s4c_commit_path_paged(k_tree, v_tree, k_pool, v_pool, block_table, cache_len, path, accept_len, features=None,
+                          features_out=None, dst_index: Optional[torch.Tensor] = None,
+                          status: Optional[torch.Tensor] = None) -> None:
+    """k_tree/v_tree [layers][B][N][Hkv][D], pools [layers][num_pages][Hkv][page][D], block_table [B][max_blocks]
+    (one table for every layer); features as in s4c_commit_path."""
+    Ly, B, N, Hkv, D = k_tree.shape
+    _, num_pages, _, page, _ = k_pool.shape
+    if tuple(k_pool.shape) != (Ly, num_pages, Hkv, page, D) or v_tree.shape != k_tree.shape or v_pool.shape != k_pool.shape:
+        raise ValueError("inconsistent shapes")
+    if block_table.dtype != torch.int32 or block_table.dim() != 2 or block_table.shape[0] != B:
+        raise TypeError("block_table must be int32 [B][max_blocks]")
+    if cache_len.dtype != torch.int32 or path.dtype != torch.int32 or accept_len.dtype != torch.int32:
+        raise TypeError("cache_len / path / accept_len must be int32")
+    max_path, max_blocks = int(path.shape[1]), int(block_table.shape[1])
+    fb = 0
+    if features is not None or features_out is not None:
+        if features is None or features_out is None or features.dtype != features_out.dtype:
+            raise TypeError("features and features_out go together and share a dtype")
+        if tuple(features.shape[:2]) != (B, N) or tuple(features_out.shape[:2]) != (B, max_path) or \
+                features.shape[2:] != features_out.shape[2:]:
+            raise ValueError("features [B][N][F] / features_out [B][max_path][F]")
+        fb = int(features[0, 0].numel() * features.element_size())
+    shape = AttnShape(B, Hkv, Hkv, D, N, max_blocks * page, _dtype_code(k_tree))
+    _check(lib().s4c_commit_path_paged(C.byref(shape), int(Ly), _ptr(k_tree), _ptr(v_tree), _ptr(k_pool), _ptr(v_pool),
+                                       _ptr(block_table), max_blocks, int(page), int(num_pages), _ptr(cache_len),
+                                       _ptr(path), _ptr(accept_len), max_path, _ptr(features), fb, _ptr(features_out),
+                                       _ptr(dst_index), _ptr(status), _stream()))
 
 
 def s4c_build_tree_workspace_size(B: int, N: int, V: int) -> int:

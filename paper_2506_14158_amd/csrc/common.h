@@ -181,6 +181,10 @@ struct CommitArgs {
     int32_t B, Hkv, N, S_cap, max_path, layers;
     int32_t row_bytes;         // D * element size
     int32_t feature_bytes;
+    // paged pools (block_table != null): k_cache / v_cache are [layers][num_pages][Hkv][page][D], one
+    // block table [B][max_blocks] serves every layer; S_cap = max_blocks << page_shift
+    const int32_t* block_table;
+    int32_t max_blocks, page_shift, num_pages;
 };
 hipError_t launch_commit(const CommitArgs& a, hipStream_t st);
 

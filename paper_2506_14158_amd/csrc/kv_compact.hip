@@ -81,7 +81,13 @@ __device__ __forceinline__ int commit_bad(const CommitArgs& a, int b, int tid, i
     const int32_t* pth = a.path + (size_t)b * a.max_path;
     int bad = (L < 0 || L >= a.max_path || base < 0 || (long long)base + L + 1 > a.S_cap);
     if (!bad)
-        for (int k = tid; k <= L; k += nthreads) bad |= (pth[k] < 0 || pth[k] >= a.N);
+        for (int k = tid; k <= L; k += nthreads) {
+            bad |= (pth[k] < 0 || pth[k] >= a.N);
+            if (a.block_table) {                       // the page of every written row must be a page of the pool
+                const int id = a.block_table[(size_t)b * a.max_blocks + ((base + k) >> a.page_shift)];
+                bad |= (id < 0 || id >= a.num_pages);
+            }
+        }
     return bad;
 }
 
@@ -119,7 +125,13 @@ __global__ __launch_bounds__(kThreads) void commit_copy_kernel(CommitArgs a) {
                 const int h = (e / vec_per_row) % a.Hkv;
                 const int k = e / (vec_per_row * a.Hkv);
                 const size_t src = (((size_t)b * a.N + pth[k]) * a.Hkv + h) * a.row_bytes + (size_t)v * 16;
-                dst[u] = (((size_t)b * a.Hkv + h) * a.S_cap + (size_t)(base + k)) * a.row_bytes + (size_t)v * 16;
+                size_t drow = ((size_t)b * a.Hkv + h) * a.S_cap + (size_t)(base + k);
+                if (a.block_table) {
+                    const int j = base + k;
+                    const size_t id = (size_t)a.block_table[(size_t)b * a.max_blocks + (j >> a.page_shift)];
+                    drow = ((id * a.Hkv + h) << a.page_shift) + (size_t)(j & ((1 << a.page_shift) - 1));
+                }
+                dst[u] = drow * a.row_bytes + (size_t)v * 16;
                 kv[u] = *(const uint4*)(ktl + src);
                 vv[u] = *(const uint4*)(vtl + src);
             }

@@ -341,14 +341,16 @@ s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
     return launch_build_tree(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
-s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
-                           void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
-                           const int32_t* accept_len, int32_t max_path, const void* features,
-                           int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
-                           void* hip_stream) {
+namespace {
+s4c_status commit_impl(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                       void* k_cache, void* v_cache, const int32_t* block_table, int32_t max_blocks, int32_t page_shift,
+                       int32_t num_pages, int32_t* cache_len, const int32_t* path, const int32_t* accept_len,
+                       int32_t max_path, const void* features, int32_t feature_bytes, void* features_out,
+                       int32_t* dst_index, int32_t* status, void* hip_stream) {
     if (!shape || !k_tree || !v_tree || !k_cache || !v_cache || !cache_len || !path || !accept_len)
         return S4C_ERR_NULL;
     s4c_attn_shape s = *shape;
+    if (block_table) s.S_cap = max_blocks << page_shift;
     if (s.Hq <= 0) s.Hq = s.Hkv;          // Hq is not used by this call
     if (s.Hkv > 0 && s.Hq % s.Hkv != 0) s.Hq = s.Hkv;
     s4c_status why;
@@ -368,8 +370,34 @@ s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const vo
     a.row_bytes = s.D * (s.dtype == S4C_F32 ? 4 : 2);
     a.feature_bytes = feats ? feature_bytes : 0;
     a.tree_layer_bytes = (size_t)s.B * s.N * s.Hkv * a.row_bytes;
-    a.cache_layer_bytes = (size_t)s.B * s.Hkv * s.S_cap * a.row_bytes;
+    a.cache_layer_bytes = block_table ? (((size_t)num_pages * s.Hkv) << page_shift) * a.row_bytes
+                                      : (size_t)s.B * s.Hkv * s.S_cap * a.row_bytes;
+    a.block_table = block_table; a.max_blocks = max_blocks; a.page_shift = page_shift; a.num_pages = num_pages;
     return launch_commit(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+}  // namespace
+
+s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                           void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
+                           const int32_t* accept_len, int32_t max_path, const void* features,
+                           int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
+                           void* hip_stream) {
+    return commit_impl(shape, layers, k_tree, v_tree, k_cache, v_cache, nullptr, 0, 0, 0, cache_len, path, accept_len,
+                       max_path, features, feature_bytes, features_out, dst_index, status, hip_stream);
+}
+
+s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
+                                 void* k_pool, void* v_pool, const int32_t* block_table, int32_t max_blocks,
+                                 int32_t page_size, int32_t num_pages, int32_t* cache_len, const int32_t* path,
+                                 const int32_t* accept_len, int32_t max_path, const void* features,
+                                 int32_t feature_bytes, void* features_out, int32_t* dst_index, int32_t* status,
+                                 void* hip_stream) {
+    if (!block_table) return S4C_ERR_NULL;
+    const int sh = page_shift_of(page_size);
+    if (sh < 0) return S4C_ERR_UNSUPPORTED;
+    if (max_blocks <= 0 || num_pages <= 0 || (long long)max_blocks * page_size > 0x7FFFFFFFll) return S4C_ERR_SHAPE;
+    return commit_impl(shape, layers, k_tree, v_tree, k_pool, v_pool, block_table, max_blocks, sh, num_pages, cache_len,
+                       path, accept_len, max_path, features, feature_bytes, features_out, dst_index, status, hip_stream);
 }
 
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,

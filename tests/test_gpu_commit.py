@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 def bits(t):
-    return t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    return t.view(torch.int16) if t.dtype in (torch.bfloat16, torch.float16) else t.view(torch.int32)
 
 
 def random_paths(rng, parent, levels):
@@ -98,3 +98,48 @@ def test_commit_path_equals_single_layer_calls_and_rejects_bad_arguments():
     with pytest.raises(B.S4CError):                       # feature rows must be whole 16-byte units
         f = torch.zeros(2, cfg.N, 5, dtype=torch.float32, device="cuda")
         B.s4c_commit_path(kt, vt, kc, vc, cl, dp, da, f, torch.zeros(2, cfg.levels, 5, dtype=torch.float32, device="cuda"))
+
+
+@pytest.mark.parametrize("dtype,Ly,Bn,Hkv,D,P,F,page", [("bf16", 4, 3, 2, 128, 300, 4096, 64), ("f32", 2, 2, 4, 64, 40, 96, 128),
+                                                        ("f16", 3, 4, 8, 128, 1000, 0, 256)])
+def test_commit_path_paged_matches_the_oracle(dtype, Ly, Bn, Hkv, D, P, F, page):
+    """Paged pools [layers][num_pages][Hkv][page][D] behind one shuffled block table: pools, cache_len,
+    destination rows, status and feature rows bit for bit; a bad page id and an overflow are flagged."""
+    rng = np.random.default_rng(Ly * 100 + Bn + page)
+    cfg = synth.scaled(synth.CONFIGS[3], B=Bn, index=0)
+    N, levels = cfg.N, cfg.levels
+    parent = synth.make_parent(cfg)
+    path, alen = random_paths(rng, parent, levels)
+    max_blocks = (P + levels + page - 1) // page
+    S_log = max_blocks * page
+    num_pages = Bn * max_blocks + 3
+    bt = rng.permutation(num_pages)[:Bn * max_blocks].reshape(Bn, max_blocks).astype(np.int32)
+    cl = rng.integers(max(0, P - 5), P + 1, size=Bn).astype(np.int32)
+    cl[-1] = S_log - 1                                   # last sequence: overflows unless its path is the root alone
+    if Bn > 2:
+        bt[1, int(cl[1]) // page] = num_pages            # sequence 1: the page it would write to is not in the pool
+    mk = (lambda shape: rng.standard_normal(shape, dtype=np.float32).astype(np.float16)) if dtype == "f16" else \
+        (lambda shape: stored_normal(rng, shape, dtype))
+    kt, vt = mk((Ly, Bn, N, Hkv, D)), mk((Ly, Bn, N, Hkv, D))
+    kp, vp = mk((Ly, num_pages, Hkv, page, D)), mk((Ly, num_pages, Hkv, page, D))
+    feats = fout = None
+    if F:
+        feats, fout = mk((Bn, N, F)), mk((Bn, levels, F))
+    dev = lambda a: None if a is None else np_to_torch(a)
+    d_kp, d_vp, d_fout = dev(kp), dev(vp), dev(fout)
+    d_cl = torch.from_numpy(cl.copy()).cuda()
+    d_dst = torch.full((Bn, levels), -9, dtype=torch.int32, device="cuda")
+    d_st = torch.full((Bn,), -9, dtype=torch.int32, device="cuda")
+    B.s4c_commit_path_paged(dev(kt), dev(vt), d_kp, d_vp, torch.from_numpy(bt).cuda(), d_cl, torch.from_numpy(path).cuda(),
+                            torch.from_numpy(alen).cuda(), dev(feats), d_fout, d_dst, d_st)
+    torch.cuda.synchronize()
+    dst, st = O.commit_path_paged(kt, vt, kp, vp, bt, cl, path, alen, feats, fout)   # in place on kp, vp, cl, fout
+    assert np.array_equal(d_st.cpu().numpy(), st) and np.array_equal(d_dst.cpu().numpy(), dst)
+    assert np.array_equal(d_cl.cpu().numpy(), cl)
+    assert torch.equal(bits(d_kp).cpu(), bits(np_to_torch(kp, "cpu")))
+    assert torch.equal(bits(d_vp).cpu(), bits(np_to_torch(vp, "cpu")))
+    if F:
+        assert torch.equal(bits(d_fout).cpu(), bits(np_to_torch(fout, "cpu")))
+    assert st[-1] == (2 if alen[-1] > 0 else 0)
+    if Bn > 2:
+        assert st[1] == 2
