@@ -348,6 +348,30 @@ def test_whole_step_bit_exact_cache(cfg):
     assert amax <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1]
 
 
+@pytest.mark.parametrize("idx", [3, 4, 5])
+def test_kv_compact_full_size(idx):
+    """The named configs at full size: the oracle's accepted paths appended by the GPU; destination
+    rows, cache_len and every byte of both caches (appended rows and everything else) checked."""
+    cfg = C[idx]
+    par = synth.make_parent(cfg)
+    at = synth.make_attn_inputs(cfg, threads=16)
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    d = to_device(cfg, par, at)
+    tv = verifier(cfg, d)
+    tv.path.copy_(torch.from_numpy(r["path"]))
+    tv.accept_len.copy_(torch.from_numpy(r["accept_len"]))
+    tv.kv_compact(d["k_tree"], d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"])
+    torch.cuda.synchronize()
+    kc, vc, cl = at.k_cache, at.v_cache, at.cache_len.copy()          # the oracle works in place on the host copies
+    dst, st = O.kv_compact(at.k_tree, at.v_tree, kc, vc, cl, r["path"], r["accept_len"])
+    assert (st == 0).all() and tv.compact_status.cpu().tolist() == [0] * cfg.B
+    assert np.array_equal(tv.dst_index.cpu().numpy(), dst)
+    assert np.array_equal(d["cache_len"].cpu().numpy(), cl)
+    assert int((cl - cfg.P).sum()) == int(r["accept_len"].sum()) + cfg.B
+    for name, host in (("k_cache", kc), ("v_cache", vc)):
+        assert torch.equal(d[name].view(torch.int16), np_to_dev(host).view(torch.int16)), name
+
+
 def test_compact_rejects_overflow_and_bad_path():
     cfg = synth.scaled(C[1], name="ovf", B=3, index=0)
     par = synth.make_parent(cfg)
