@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, help="1..5 (BASELINE configs); 5 is the headline workload")
+    ap.add_argument("--config", type=int, default=5, help="1..5 (the five benchmark configs); 5 is the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="re-use one input copy every step (cache-warm numbers)")
     ap.add_argument("--resample", action="store_true",
