@@ -90,6 +90,33 @@ def test_accept_and_compact_host_errors(L):
     assert cmp_(mp=0) == -2
 
 
+def test_paged_and_multi_layer_host_errors(L):
+    """Every check below fails before any launch (no GPU needed): null pointers, page sizes that are not
+    powers of two >= 64, a logical capacity that disagrees with the block table, layer counts."""
+    one = C.c_void_p(256)
+    s = shape(S_cap=64 * 128)
+    pa = lambda sh=s, bt=one, mb=64, ps=128, npg=200: L.s4c_tree_attn_paged(
+        C.byref(sh), one, one, one, one, one, bt, mb, ps, npg, one, one, 4096, 0.0, one, None, one, 1 << 30, None)
+    assert pa(bt=None) == -1
+    assert pa(ps=96) == -3 and pa(ps=32) == -3
+    assert pa(mb=0) == -2 and pa(npg=0) == -2
+    assert pa(mb=63) == -2                                   # S_cap != max_blocks * page_size
+    cp = lambda sh=s, bt=one, mb=64, ps=128, npg=200, mp=4: L.s4c_kv_compact_paged(
+        C.byref(sh), one, one, one, one, bt, mb, ps, npg, one, one, one, mp, None, None, None)
+    assert cp(bt=None) == -1 and cp(ps=100) == -3 and cp(mb=0) == -2 and cp(mp=0) == -2
+    cm = lambda sh=s, layers=4, kt=one, feats=None, fo=None, fb=0, mp=4: L.s4c_commit_path(
+        C.byref(sh), layers, kt, one, one, one, one, one, one, mp, feats, fb, fo, None, None, None)
+    assert cm(kt=None) == -1 and cm(layers=0) == -2 and cm(layers=70000) == -2 and cm(mp=0) == -2
+    assert cm(feats=one, fo=None, fb=64) == -1               # features and features_out go together
+    assert cm(feats=one, fo=one, fb=24) == -2                # rows must be multiples of 16 bytes
+    cmp_ = lambda bt=one, ps=128, mb=64, npg=200, layers=4: L.s4c_commit_path_paged(
+        C.byref(s), layers, one, one, one, one, bt, mb, ps, npg, one, one, one, 4, None, 0, None, None, None, None)
+    assert cmp_(bt=None) == -1 and cmp_(ps=48) == -3 and cmp_(mb=0) == -2 and cmp_(layers=0) == -2
+    dl = lambda T=64, H=64, Hout=256, dt=1, e=one: L.s4c_draft_linear(T, H, Hout, dt, e, one, one, None, one, None)
+    assert dl(e=None) == -1 and dl(T=0) == -2 and dl(dt=0) == -3 and dl(H=40) == -3 and dl(Hout=100) == -3
+    assert dl(e=C.c_void_p(8)) == -2                          # 16-byte alignment
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libs4c.so")
