@@ -30,7 +30,9 @@ class TreeVerifier:
         self.compact_status = torch.zeros(B, **i32)
         self.attn_ws = _b.alloc_workspace(_b.s4c_tree_attn_workspace_size(self.shape, max_cache_len), device)
         self.accept_ws = _b.alloc_workspace(_b.s4c_accept_path_workspace_size(B, N, V), device)
-        self.resample_ws = None     # allocated on the first accept_resample call
+        # sequential acceptance: the exchange slots of the workgroup teams (a few hundred KB at most), allocated
+        # here so that no call allocates later (a step may be under graph capture)
+        self.resample_ws = _b.alloc_workspace(max(256, _b.s4c_accept_resample_workspace_size(B, N, V, max_path)), device)
         self.num_splits = _b.s4c_tree_attn_num_splits(self.shape, max_cache_len)
 
     def tree_attn(self, q, k_tree, v_tree, k_cache, v_cache, cache_len, parent, scale: float = 0.0):
@@ -44,9 +46,6 @@ class TreeVerifier:
 
     def accept_resample(self, logits, draft_probs, parent, tokens, uniforms, u_resample, temperature=1.0):
         """Sibling-sequential rule with the correction token; same outputs as accept_path."""
-        if self.resample_ws is None:
-            self.resample_ws = _b.alloc_workspace(
-                max(256, _b.s4c_accept_resample_workspace_size(self.B, self.N, self.V, self.max_path)), logits.device)
         _b.s4c_accept_resample(logits, draft_probs, parent, tokens, uniforms, u_resample, self.max_path, self.path,
                                self.accept_len, self.accepted_tokens, self.bonus_token, self.resample_ws, temperature,
                                self.accept_status)
