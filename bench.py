@@ -186,7 +186,10 @@ def main():
     es = cfg.es
     kv_bytes = cfg.B * cfg.Hkv * (cfg.P + cfg.N) * cfg.D * 2 * es
     flops = 4.0 * cfg.B * cfg.Hq * cfg.N * (cfg.P + cfg.N) * cfg.D
-    logits_bytes = cfg.B * cfg.N * cfg.V * es
+    # the acceptance scan reads every logits row in greedy mode (the bonus token may come from any row) and
+    # only the rows of nodes with children in stochastic mode (a leaf's row verifies nobody)
+    accept_rows = cfg.B * cfg.N if cfg.mode == "greedy" else int(sum((np.bincount(p[1:], minlength=cfg.N) > 0).sum() for p in par))
+    logits_bytes = accept_rows * cfg.V * es
     ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
     if cfg.dtype in ("bf16", "f16") and flops / kv_bytes > ridge:
         roof = {"bound": "mfma", "achieved": flops / t_attn / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
@@ -219,7 +222,7 @@ def main():
                     "attn_TFLOPs": flops / t_attn / 1e12, "frac_of_mfma_peak": flops / t_attn / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                     "flop_per_kv_byte": flops / kv_bytes},
         "phases_ms": {"tree_attn": t_attn * 1e3, "accept_path": t_acc * 1e3, "kv_compact": t_cmp * 1e3},
-        "accept_path_GBps": logits_bytes / t_acc / 1e9,
+        "accept_path_GBps": logits_bytes / t_acc / 1e9, "accept_rows_scanned": accept_rows,
         "paper_context": "paper reports 2.26x-2.60x end-to-end vs autoregressive decoding (A100-40GB / 4xRTX4090, fp16, batch 1)",
     }
     # what plain kernels reach on this GPU (context for the published peaks above)

@@ -1,6 +1,7 @@
 // Path acceptance (paper Sec. 3.2: per-node test, then the longest accepted path).
 //
-// Kernel 1 (row_stats): the HBM-bound part.  Each workgroup reads a segment of consecutive
+// Kernel 1 (row_stats): the HBM-bound part (all rows in greedy mode, whose bonus token may come
+// from any row; in stochastic mode only the rows of nodes that have children).  Each workgroup reads a segment of consecutive
 // 8192-logit chunks of one logits row exactly once with 16-byte loads (the next chunk in flight
 // while the current one is reduced in registers), and reduces
 //   (max value, lowest index attaining it)   -- argmax, ties to the lowest token id
@@ -28,6 +29,12 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(AcceptArgs a) {
     const int ch0 = sg * a.seg, ch1 = min(a.chunks, ch0 + a.seg);
     const bool vec_ok = ((((uintptr_t)base) & 15) == 0);
     const bool stochastic = a.mode == S4C_STOCHASTIC;
+    if (stochastic) {
+        // A leaf's row verifies no node, and the stochastic rule returns no bonus token: not read.
+        const int b = row / a.N, node = row % a.N;
+        const int has_child = (tid < a.N) && (a.parent[(size_t)b * a.N + tid] == node);
+        if (!__syncthreads_or(has_child)) return;
+    }
 
     // per-thread running state over the segment's chunks: argmax (lowest index among equals: the
     // scan ascends and '>' is strict), and a sum of exponentials relative to the thread's own
@@ -126,10 +133,16 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
     if (i == 0) s_best = 0;
     bad = __syncthreads_or(bad);
 
-    // ---- combine the chunk statistics of row i
+    // ---- combine the chunk statistics of row i (stochastic mode: only rows of nodes with children
+    // were scanned)
+    __shared__ int32_t s_has[kMaxNodes];
+    s_has[i] = 0;
+    __syncthreads();
+    if (i >= 1 && i < N && spar[i] >= 0 && spar[i] < i) s_has[spar[i]] = 1;      // same value from every child
+    __syncthreads();
     float m = -INFINITY, S = 0.f;
     int32_t g = 0x7FFFFFFF;
-    if (i < N) {
+    if (i < N && (a.mode == S4C_GREEDY || s_has[i])) {
         const size_t o = ((size_t)b * N + i) * a.nseg;
         for (int c = 0; c < a.nseg; ++c) {
             const float v = a.ws_max[o + c];
@@ -138,8 +151,8 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
         if (a.mode == S4C_STOCHASTIC)
             for (int c = 0; c < a.nseg; ++c)
                 S += a.ws_sum[o + c] * fast_exp2((a.ws_max[o + c] - m) * a.inv_temp_log2);
-        s_g[i] = g;
     }
+    if (i < N) s_g[i] = g;
     __shared__ float s_m[kMaxNodes], s_S[kMaxNodes];
     if (i < N) { s_m[i] = m; s_S[i] = S; }
     __syncthreads();
