@@ -122,27 +122,35 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
     __shared__ int32_t s_ok[kMaxNodes];
     __shared__ int32_t s_g[kMaxNodes];
     __shared__ int32_t s_best;
+    __shared__ int32_t s_tok[kMaxNodes];
 
-    // ---- tree validation: node 0 is the only root, parents precede children
+    // ---- everything node i needs that does not depend on another load is requested up front (the
+    // kernel is a chain of dependent memory latencies, not of work)
     int bad = 0;
+    int tok = -1, par_i = -1;
+    float u_i = 0.f, pd_i = 0.f;
     if (i < N) {
-        const int p = a.parent[(size_t)b * N + i];
+        const int p = par_i = a.parent[(size_t)b * N + i];
+        tok = a.tokens[(size_t)b * N + i];
+        if (a.mode == S4C_STOCHASTIC && i > 0) {
+            u_i = a.uniforms[(size_t)b * N + i];
+            pd_i = a.p_draft[(size_t)b * N + i];
+        }
+        // tree validation: node 0 is the only root, parents precede children
         spar[i] = p;
+        s_tok[i] = tok;
         bad = (i == 0) ? (p != -1) : (p < 0 || p >= i);
     }
-    if (i == 0) s_best = 0;
-    bad = __syncthreads_or(bad);
-
-    // ---- combine the chunk statistics of row i (stochastic mode: only rows of nodes with children
-    // were scanned)
-    __shared__ int32_t s_has[kMaxNodes];
-    s_has[i] = 0;
-    __syncthreads();
-    if (i >= 1 && i < N && spar[i] >= 0 && spar[i] < i) s_has[spar[i]] = 1;      // same value from every child
-    __syncthreads();
+    // the target logit of this node's token in its parent's row (needs only parent and token)
+    float lx = 0.f;
+    if (a.mode == S4C_STOCHASTIC && i > 0 && i < N && !bad && tok >= 0 && tok < a.V)
+        lx = to_f32<T>(((const T*)a.logits)[((size_t)b * N + par_i) * a.V + tok]);
+    // ---- combine the segment statistics of row i.  In stochastic mode only the rows of nodes with
+    // children were scanned; a leaf's slots hold whatever the workspace held, and nothing below reads
+    // a leaf's statistics (a node is tested against its PARENT's row; no bonus token in that mode).
     float m = -INFINITY, S = 0.f;
     int32_t g = 0x7FFFFFFF;
-    if (i < N && (a.mode == S4C_GREEDY || s_has[i])) {
+    if (i < N) {
         const size_t o = ((size_t)b * N + i) * a.nseg;
         for (int c = 0; c < a.nseg; ++c) {
             const float v = a.ws_max[o + c];
@@ -151,8 +159,11 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
         if (a.mode == S4C_STOCHASTIC)
             for (int c = 0; c < a.nseg; ++c)
                 S += a.ws_sum[o + c] * fast_exp2((a.ws_max[o + c] - m) * a.inv_temp_log2);
+        s_g[i] = g;
     }
-    if (i < N) s_g[i] = g;
+    if (i == 0) s_best = 0;
+    bad = __syncthreads_or(bad);
+
     __shared__ float s_m[kMaxNodes], s_S[kMaxNodes];
     if (i < N) { s_m[i] = m; s_S[i] = S; }
     __syncthreads();
@@ -163,15 +174,13 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
         int ok = 1;
         if (i > 0) {
             const int p = spar[i];
-            const int tok = a.tokens[(size_t)b * N + i];
             if (a.mode == S4C_GREEDY) {
                 ok = (tok == s_g[p]);
             } else if (tok < 0 || tok >= a.V) {
                 ok = 0;
             } else {
-                const float lx = to_f32<T>(((const T*)a.logits)[((size_t)b * N + p) * a.V + tok]);
                 const float pt = fast_exp2((lx - s_m[p]) * a.inv_temp_log2) / s_S[p];
-                const float lhs = a.uniforms[(size_t)b * N + i] * a.p_draft[(size_t)b * N + i];
+                const float lhs = u_i * pd_i;
                 ok = (lhs < pt);
             }
         }
@@ -206,7 +215,7 @@ __global__ __launch_bounds__(kMaxNodes) void path_kernel(AcceptArgs a) {
         int node = i;
         for (int k = L; k >= 1; --k) {
             pth[k] = node;
-            atk[k - 1] = a.tokens[(size_t)b * N + node];
+            atk[k - 1] = s_tok[node];
             node = spar[node];
         }
         a.accept_len[b] = L;
