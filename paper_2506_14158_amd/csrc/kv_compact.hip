@@ -15,14 +15,20 @@ constexpr int kBatch = 4;       // independent 16-byte copies in flight per thre
 
 __global__ __launch_bounds__(kThreads) void kv_compact_kernel(CompactArgs a) {
     const int b = blockIdx.x, tid = threadIdx.x;
+    const int32_t* pth = a.path + (size_t)b * a.max_path;
+    // the three loads that everything else depends on go out together (path entries before the
+    // accepted length is known; a real path has at most kMaxNodes nodes, longer ones are read in place)
+    __shared__ int32_t s_path[kMaxNodes];
     const int L = a.accept_len[b];
     const int base = a.cache_len[b];
-    const int32_t* pth = a.path + (size_t)b * a.max_path;
+    if (tid < kMaxNodes) s_path[tid] = (tid < a.max_path) ? pth[tid] : -1;
+    __syncthreads();
 
+    auto node_at = [&](int k) { return k < kMaxNodes ? s_path[k] : pth[k]; };
     int bad = (L < 0 || L >= a.max_path || base < 0 || (long long)base + L + 1 > a.S_cap);
     if (!bad)
         for (int k = tid; k <= L; k += kThreads) {
-            bad |= (pth[k] < 0 || pth[k] >= a.N);
+            bad |= (node_at(k) < 0 || node_at(k) >= a.N);
             if (a.block_table) {                       // the page of every written row must be a page of the pool
                 const int id = a.block_table[(size_t)b * a.max_blocks + ((base + k) >> a.page_shift)];
                 bad |= (id < 0 || id >= a.num_pages);
@@ -48,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void kv_compact_kernel(CompactArgs a) {
                 const int v = e % vec_per_row;
                 const int h = (e / vec_per_row) % a.Hkv;
                 const int k = e / (vec_per_row * a.Hkv);
-                const size_t src = (((size_t)b * a.N + pth[k]) * a.Hkv + h) * a.row_bytes + (size_t)v * 16;
+                const size_t src = (((size_t)b * a.N + node_at(k)) * a.Hkv + h) * a.row_bytes + (size_t)v * 16;
                 size_t drow = ((size_t)b * a.Hkv + h) * a.S_cap + (size_t)(base + k);
                 if (a.block_table) {
                     const int j = base + k;
