@@ -124,7 +124,8 @@ size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V);
  *   bonus_token     [B] greedy: argmax of the last path node's row; stochastic: -1
  *   status          [B] nullable; S4C_SEQ_BAD_TREE if parent[] is malformed or a node is deeper
  *                   than max_path-1: then accept_len = 0, path = [0], bonus = -1.
- * Softmax statistics are fp32. */
+ * Softmax statistics are fp32.  In STOCHASTIC mode the logits rows of leaf nodes are never read (they
+ * verify no node and that mode returns no bonus token); in GREEDY mode every row may be read. */
 s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
                            float temperature, const void* logits, const int32_t* parent,
                            const int32_t* tokens, const float* p_draft, const float* uniforms,
