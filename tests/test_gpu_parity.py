@@ -288,6 +288,27 @@ def test_accept_path_full_size(idx):
     print("cfg%d accept_len" % idx, r["accept_len"].tolist())
 
 
+def test_stochastic_acceptance_never_reads_leaf_rows():
+    """A leaf's logits row verifies no node and the stochastic rule returns no bonus token: with every
+    leaf row overwritten by NaN patterns the result must still be the oracle's on the clean rows."""
+    cfg = synth.scaled(C[3], name="leaf-nan", B=3, V=9000, index=0)
+    par = synth.make_parent(cfg)
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    lg = ac.logits.copy()
+    for b in range(cfg.B):
+        has_child = np.zeros(cfg.N, dtype=bool)
+        has_child[par[b, 1:]] = True
+        lg[b, ~has_child] = 0x7FC0                       # bf16 quiet NaN
+        assert (~has_child).sum() > 0
+    ac2 = synth.AcceptInputs(lg, ac.tokens, ac.p_draft, ac.uniforms)
+    tv = run_accept(cfg, par, ac2)
+    assert np.array_equal(tv.accept_status.cpu().numpy(), r["status"])
+    assert np.array_equal(tv.path.cpu().numpy(), r["path"])
+    assert np.array_equal(tv.accept_len.cpu().numpy(), r["accept_len"])
+    assert np.array_equal(tv.accepted_tokens.cpu().numpy(), r["accepted_tokens"])
+    assert (tv.bonus_token.cpu().numpy() == -1).all()
+
+
 def test_accept_argmax_ties_and_hand_example():
     """bf16 logits tie often; the lowest token id must win on the GPU exactly as in the oracle."""
     rng = np.random.default_rng(3)
