@@ -11,7 +11,13 @@
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller; `shape` structs are HOST
- *     pointers.  The library allocates nothing and keeps no state.
+ *     pointers.  The library allocates nothing.  What it keeps between calls is per-GPU set-up
+ *     only: which of its kernels already had their dynamic-LDS limit raised and the compute-unit
+ *     count it sizes launches by.
+ *   - Q, K, V, the caches / pools and `out` must be 16-byte aligned (checked: S4C_ERR_SHAPE);
+ *     logits rows may have any alignment.  Floating-point inputs must be finite (no NaN, no
+ *     infinity): the kernels are compiled without NaN handling, and a non-finite input gives an
+ *     unspecified (but in-bounds) result for the sequences that read it.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t, may be NULL for the default
  *     stream) and never synchronise; they may be chained on one stream
  *     (s4c_accept_path -> s4c_kv_compact reads `path` on the device).
@@ -50,7 +56,7 @@ typedef enum { S4C_GREEDY = 0, S4C_STOCHASTIC = 1 } s4c_accept_mode;
 #define S4C_SEQ_BAD_LEN  2     /* cache_len out of range / accepted rows do not fit S_cap */
 #define S4C_SEQ_TIMEOUT  4     /* s4c_accept_resample: the workgroups of a sequence could not exchange
                                   their partial sums within the poll limit (GPU shared with a kernel
-                                  that never ends); accept_len = 0, bonus = -1 */
+                                  that never ends); accept_len = 0, path = [0], bonus = -1 */
 
 typedef struct {
     int32_t B;       /* sequences */
@@ -156,7 +162,11 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
  *              partial sums that the workgroups sharing one sequence exchange, so two calls that
  *              may overlap in time must not share it.
  * Arithmetic is fp64 (row maxima exact).  V <= 2^21.  The kernel polls device memory with a
- * bounded number of tries (S4C_SEQ_TIMEOUT); it needs at most 256 workgroups resident at once. */
+ * bounded number of tries (S4C_SEQ_TIMEOUT); it needs at most 256 workgroups resident at once.
+ * One workgroup per sequence writes all of that sequence's outputs, so a flagged sequence never
+ * carries a partial result.  The environment variable S4C_RESAMPLE_SPIN_LIMIT (an integer >= 0,
+ * read at every call) replaces the number of tries; 0 makes every exchange between several
+ * workgroups give up at once, which exercises the flagged path on a healthy GPU. */
 size_t s4c_accept_resample_workspace_size(int32_t B, int32_t N, int32_t V, int32_t max_path);
 s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, float temperature,
                                const void* logits, const float* draft_probs, const int32_t* parent,
@@ -247,23 +257,8 @@ s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, co
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
                             const void* W, const void* bias, void* out, void* hip_stream);
 
-/* Measurement probes: no part of the verification step.  They give the benchmark the streaming-read
- * rate and the dense bf16 matrix-core rate that plain kernels reach on the GPU at hand, next to
- * the published peaks the rooflines are priced against.  The caller times them with events.
- *   s4c_probe_stream_read  reads `bytes` (>= 16, buffer 16-byte aligned, device) once with 16-byte
- *                          loads from 4096 workgroups; sink: one device float (left alone).
- *   s4c_probe_mfma_bf16    256 workgroups x 8 wavefronts x iters x 32 v_mfma_f32_32x32x16_bf16 on
- *                          register operands that are one constant (random_operands = 0) or drawn
- *                          from an approximate standard normal (1) -- the rate depends on the data,
- *                          because the clock follows the multipliers' switching power.
- *                          sink: >= s4c_probe_mfma_sink_bytes() device bytes (overwritten);
- *                          *flops (host, nullable) receives the FLOP count of the launch. */
-s4c_status s4c_probe_stream_read(const void* buffer, size_t bytes, float* sink, void* hip_stream);
-size_t s4c_probe_mfma_sink_bytes(void);
-s4c_status s4c_probe_mfma_bf16(int32_t random_operands, int32_t iters, float* sink, double* flops, void* hip_stream);
-
-/* Static, never NULL. */
-const char* s4c_strerror(s4c_status code);
+/* Text for a status code (any integer: unknown codes get "unknown status").  Static, never NULL. */
+const char* s4c_strerror(int code);
 
 /* Number of KV splits s4c_tree_attn uses for this shape (1 = single pass); for reporting. */
 int32_t s4c_tree_attn_num_splits(const s4c_attn_shape* shape, int32_t max_cache_len);

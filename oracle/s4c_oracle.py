@@ -33,7 +33,9 @@ class _Shape(C.Structure):
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # S4C_ORACLE_LIB: a library somebody else built from the same source (the sanitizer test's
+        # instrumented build); otherwise build in place if stale
+        _lib = C.CDLL(os.environ.get("S4C_ORACLE_LIB") or build())
         for name in ("oracle_tree_attn", "oracle_tree_attn_sampled", "oracle_accept_path",
                      "oracle_row_stats", "oracle_kv_compact", "oracle_num_threads", "oracle_accept_resample", "oracle_commit_path", "oracle_build_tree", "oracle_draft_linear", "oracle_paged_gather", "oracle_kv_compact_paged", "oracle_decode", "oracle_commit_path_paged"):
             getattr(_lib, name).restype = C.c_int

@@ -16,12 +16,12 @@ LIB_PATH = os.path.join(_PKG, "libs4c.so")
 
 S4C_F32, S4C_BF16, S4C_F16 = 0, 1, 2
 S4C_GREEDY, S4C_STOCHASTIC = 0, 1
-S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN = 1, 2
+S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN, S4C_SEQ_TIMEOUT = 1, 2, 4
 
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged", "s4c_probe_stream_read", "s4c_probe_mfma_sink_bytes", "s4c_probe_mfma_bf16")
+           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged")
 
 
 class S4CError(RuntimeError):
@@ -84,12 +84,6 @@ def lib() -> C.CDLL:
             C.c_int32] + [C.c_void_p] * 3
         L.s4c_draft_linear.restype = C.c_int
         L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6
-        L.s4c_probe_stream_read.restype = C.c_int
-        L.s4c_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
-        L.s4c_probe_mfma_sink_bytes.restype = C.c_size_t
-        L.s4c_probe_mfma_sink_bytes.argtypes = []
-        L.s4c_probe_mfma_bf16.restype = C.c_int
-        L.s4c_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         L.s4c_strerror.restype = C.c_char_p
         L.s4c_strerror.argtypes = [C.c_int]
         _lib = L
@@ -209,9 +203,7 @@ def s4c_accept_path_workspace_size(B: int, N: int, V: int) -> int:
     return int(lib().s4c_accept_path_workspace_size(B, N, V))
 
 
-def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, accept_len, accepted_tokens,
-                    bonus_token, workspace, p_draft=None, uniforms=None, temperature: float = 1.0,
-                    status: Optional[torch.Tensor] = None) -> None:
+def _accept_checks(logits, parent, tokens, max_path, path, accept_len, accepted_tokens, bonus_token, p_draft, uniforms):
     B, N, V = logits.shape
     for t in (parent, tokens):
         if t.dtype != torch.int32 or tuple(t.shape) != (B, N):
@@ -224,6 +216,13 @@ def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, acce
     for t in (p_draft, uniforms):
         if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (B, N)):
             raise TypeError("p_draft / uniforms must be float32 [B][N]")
+    return B, N, V
+
+
+def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, accept_len, accepted_tokens,
+                    bonus_token, workspace, p_draft=None, uniforms=None, temperature: float = 1.0,
+                    status: Optional[torch.Tensor] = None) -> None:
+    B, N, V = _accept_checks(logits, parent, tokens, max_path, path, accept_len, accepted_tokens, bonus_token, p_draft, uniforms)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().s4c_accept_path(B, N, V, _dtype_code(logits), int(mode), float(temperature), _ptr(logits),
                                  _ptr(parent), _ptr(tokens), _ptr(p_draft), _ptr(uniforms), int(max_path),
@@ -363,20 +362,6 @@ def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
             raise TypeError("s4c_draft_linear takes bfloat16 or float16 tensors of one type")
     _check(lib().s4c_draft_linear(T, H, Hout, _dtype_code(e), _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out), _stream()))
     return out
-
-
-def s4c_probe_stream_read(buffer: torch.Tensor, sink: torch.Tensor) -> None:
-    """Enqueue one streaming read of `buffer` (measurement probe; time it with events)."""
-    _check(lib().s4c_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink), _stream()))
-
-
-def s4c_probe_mfma_bf16(random_operands: bool, iters: int, sink: torch.Tensor) -> float:
-    """Enqueue the matrix-core probe; returns the FLOP count of the launch."""
-    if sink.numel() * sink.element_size() < lib().s4c_probe_mfma_sink_bytes():
-        raise ValueError("sink too small")
-    flops = C.c_double(0.0)
-    _check(lib().s4c_probe_mfma_bf16(int(bool(random_operands)), int(iters), _ptr(sink), C.byref(flops), _stream()))
-    return float(flops.value)
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:

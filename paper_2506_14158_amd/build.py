@@ -21,13 +21,15 @@ FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build_lib(verbose: bool = False, lib: str = LIB, obj_dir: str = OBJ, extra_flags=()) -> str:
+    """Compile csrc/*.hip (in parallel) and link them into `lib`.  `extra_flags` are appended to the
+    compile and link lines (the sanitizer test builds an instrumented copy elsewhere this way)."""
+    os.makedirs(obj_dir, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
     def cc(src):
-        obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
-        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
+        cmd = [HIPCC] + FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, r.stderr[-8000:]))
@@ -37,11 +39,24 @@ def build_lib(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(cc, srcs))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + list(extra_flags) + ["-o", lib] + objs,
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr[-4000:])
-    return LIB
+    return lib
+
+
+PROBE_SRC = os.path.join(PKG, "probe", "probes.hip")
+PROBE_LIB = os.path.join(PKG, "libs4c_probe.so")
+
+
+def build_probe_lib() -> str:
+    """The benchmark's measurement probes: a library of their own, not part of libs4c.so."""
+    cmd = [HIPCC] + FLAGS + ["-I" + os.path.join(PKG, "probe"), "-shared", PROBE_SRC, "-o", PROBE_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on %s:\n%s" % (PROBE_SRC, r.stderr[-8000:]))
+    return PROBE_LIB
 
 
 C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "verify_step.c")
@@ -63,4 +78,5 @@ def build_c_client() -> str:
 
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_probe_lib())
     print(build_c_client())

@@ -9,7 +9,10 @@
 // (one relaxed 64-bit atomic store and G polled atomic loads; a slot still holding the
 // sentinel has not been written yet).  All G workgroups then add the partials in slot order,
 // obtain bit-identical sums and so take the same branches without any other communication.
-// The poll is bounded: a team that cannot complete an exchange flags the sequence and exits.
+// The poll is bounded: a workgroup that cannot complete an exchange exits.  Workgroup 0 of the team
+// is the only one that writes the sequence's outputs (the owner of the correction token hands it over
+// through one more slot), so what the caller sees is either a complete result or, if workgroup 0
+// itself gave up anywhere, the flagged empty one -- never a mixture.
 //
 // Everything is kept unnormalised so no row is ever rewritten:
 //   a_0[v] = exp((l[v] - max l) / T)              S_0 = sum_v a_0[v]        (target row)
@@ -36,7 +39,7 @@ constexpr int kMaxBlocks = 4096;       // => V <= 2^21
 constexpr int kMaxTeam = 16;           // workgroups per sequence
 constexpr int kTeamBudget = 256;       // teams * team size never exceeds this many workgroups
 constexpr uint64_t kEmpty = ~0ull;     // slot not written yet (a NaN pattern no partial result has)
-constexpr int kSpinLimit = 1 << 20;    // polls (each followed by a short sleep) before giving up
+constexpr int kSpinLimit = 1 << 20;    // default number of polls (each followed by a short sleep) before giving up
 
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
@@ -117,7 +120,7 @@ __device__ __forceinline__ void weights8(const Row& r, int base, float m, double
 // gotB[0..G) hold everyone's words (the same in all workgroups of the team).  *s_fail is set
 // (and stays set) if some word never arrived.
 __device__ __forceinline__ void team_exchange(uint64_t* slots, int g, int G, bool two, uint64_t mineA, uint64_t mineB,
-                                              uint64_t* gotA, uint64_t* gotB, int* s_fail, int tid) {
+                                              uint64_t* gotA, uint64_t* gotB, int* s_fail, int tid, int spin_limit) {
     if (G == 1) {
         if (tid == 0) { gotA[0] = mineA; gotB[0] = mineB; }
         __syncthreads();
@@ -129,7 +132,7 @@ __device__ __forceinline__ void team_exchange(uint64_t* slots, int g, int G, boo
     }
     if (tid < (two ? 2 * G : G)) {
         uint64_t v = __hip_atomic_load(&slots[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int spin = 0; v == kEmpty && spin < kSpinLimit; ++spin) {
+        for (int spin = 0; v == kEmpty && spin < spin_limit; ++spin) {
             __builtin_amdgcn_s_sleep(2);
             v = __hip_atomic_load(&slots[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -197,15 +200,21 @@ __global__ __launch_bounds__(kThreads) void accept_resample_kernel(ResampleArgs 
     uint64_t* slots = a.slots + (size_t)b * a.max_pass * 2 * G;   // [max_pass][2][G]
     int pass = 0;
 
-    // an exchange that cannot complete (or more exchanges than the slot array holds, which a
-    // valid tree cannot need): flag the sequence; uniform across the workgroup
-#define S4C_TEAM_CHECK()                                                       \
-    if (s_fail || pass > a.max_pass) {                                         \
-        if (tid == 0) {                                                        \
-            if (a.status) a.status[b] = S4C_SEQ_TIMEOUT;                       \
-            if (g == 0) { a.accept_len[b] = 0; a.bonus_token[b] = -1; }        \
-        }                                                                      \
-        return;                                                                \
+    // An exchange that cannot complete (or more exchanges than the slot array holds, which a valid
+    // tree cannot need): the workgroup leaves; workgroup 0 flags the sequence and empties its outputs
+    // on the way out.  The condition is uniform across the workgroup.
+#define S4C_TEAM_CHECK()                                                                                   \
+    if (s_fail || pass > a.max_pass) {                                                                     \
+        if (g == 0) {                                                                                      \
+            __syncthreads();   /* thread 0's earlier path entries are ordered before the reset */          \
+            for (int k = tid; k < a.max_path; k += kThreads) { pth[k] = (k == 0) ? 0 : -1; atk[k] = -1; }  \
+            if (tid == 0) {                                                                                \
+                if (a.status) a.status[b] = S4C_SEQ_TIMEOUT;                                               \
+                a.accept_len[b] = 0;                                                                       \
+                a.bonus_token[b] = -1;                                                                     \
+            }                                                                                              \
+        }                                                                                                  \
+        return;                                                                                            \
     }
 
     Row row;
@@ -257,7 +266,7 @@ __global__ __launch_bounds__(kThreads) void accept_resample_kernel(ResampleArgs 
         ++pass;
         S4C_TEAM_CHECK();
         team_exchange(slots + (size_t)(pass - 1) * 2 * G, g, G, true, (uint64_t)__float_as_uint(mg), f64_to_bits(sg),
-                      s_gotA, s_gotB, &s_fail, tid);
+                      s_gotA, s_gotB, &s_fail, tid, a.spin_limit);
         S4C_TEAM_CHECK();
         m = bits_to_f32(s_gotA[0]);
         for (int i = 1; i < G; ++i) m = fmaxf(m, bits_to_f32(s_gotA[i]));
@@ -303,7 +312,7 @@ __global__ __launch_bounds__(kThreads) void accept_resample_kernel(ResampleArgs 
             for (int w = 0; w < kWaves; ++w) zg += s_red[w];
             ++pass;
             S4C_TEAM_CHECK();
-            team_exchange(slots + (size_t)(pass - 1) * 2 * G, g, G, false, f64_to_bits(zg), 0, s_gotA, s_gotB, &s_fail, tid);
+            team_exchange(slots + (size_t)(pass - 1) * 2 * G, g, G, false, f64_to_bits(zg), 0, s_gotA, s_gotB, &s_fail, tid, a.spin_limit);
             S4C_TEAM_CHECK();
             double t = 0.0;
             for (int i = 0; i < G; ++i) t += bits_to_f64(s_gotA[i]);
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void accept_resample_kernel(ResampleArgs 
     for (int blk = gblk0; blk < gblk1; ++blk) slice += s_blk[blk - gblk0];
     ++pass;
     S4C_TEAM_CHECK();
-    team_exchange(slots + (size_t)(pass - 1) * 2 * G, g, G, false, f64_to_bits(slice), 0, s_gotA, s_gotB, &s_fail, tid);
+    team_exchange(slots + (size_t)(pass - 1) * 2 * G, g, G, false, f64_to_bits(slice), 0, s_gotA, s_gotB, &s_fail, tid, a.spin_limit);
     S4C_TEAM_CHECK();
     // owning workgroup: the first whose inclusive prefix (slices added in order) exceeds tgt
     double total = 0.0;
@@ -352,44 +361,73 @@ __global__ __launch_bounds__(kThreads) void accept_resample_kernel(ResampleArgs 
         run += v;
     }
     if (gsel < 0) { gsel = glast; gexcl = glexcl; }     // tgt >= total can only come from rounding
-    if (g == 0 && tid == 0) a.accept_len[b] = L;
-    if (g != gsel) return;
-    // owning block inside the slice, same rule; every thread runs the same loop
-    int bsel = -1, blast = gblk0;
-    double bexcl = gexcl, r2 = gexcl, blexcl = gexcl;
-    for (int blk = gblk0; blk < gblk1; ++blk) {
-        const double v = s_blk[blk - gblk0];
-        if (v > 0.0) { blast = blk; blexcl = r2; }
-        if (bsel < 0 && r2 + v > tgt) { bsel = blk; bexcl = r2; }
-        r2 += v;
-    }
-    if (bsel < 0) { bsel = blast; bexcl = blexcl; }
-    if (wave == 0) {
-        // owning lane, then owning token
-        double w8[8];
-        weights8<T>(row, bsel * kBlock + lane * 8, m, invT, sS, j, w8);
-        double ls = 0.0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) ls += w8[k];
-        const double incl = wave_incl_scan(ls, lane);
-        const bool hit = (bexcl + incl > tgt) && ls > 0.0;
-        const unsigned long long hits = __ballot(hit);
-        const unsigned long long pos = __ballot(ls > 0.0);
-        int lsel;
-        if (hits) lsel = __ffsll((long long)hits) - 1;
-        else lsel = 63 - __clzll((long long)(pos ? pos : 1ull));      // rounding: last lane with mass
-        if (lane == lsel) {
-            double r3 = bexcl + (incl - ls);
-            int pick = -1, lastpos = -1;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                r3 += w8[k];
-                if (w8[k] > 0.0) lastpos = k;
-                if (pick < 0 && r3 > tgt && w8[k] > 0.0) pick = k;
-            }
-            if (pick < 0) pick = max(lastpos, 0);
-            a.bonus_token[b] = bsel * kBlock + lane * 8 + pick;
+    if (g != gsel && g != 0) return;
+    __shared__ int s_token;
+    if (tid == 0) s_token = -1;
+    __syncthreads();
+    if (g == gsel) {
+        // owning block inside the slice, same rule; every thread runs the same loop
+        int bsel = -1, blast = gblk0;
+        double bexcl = gexcl, r2 = gexcl, blexcl = gexcl;
+        for (int blk = gblk0; blk < gblk1; ++blk) {
+            const double v = s_blk[blk - gblk0];
+            if (v > 0.0) { blast = blk; blexcl = r2; }
+            if (bsel < 0 && r2 + v > tgt) { bsel = blk; bexcl = r2; }
+            r2 += v;
         }
+        if (bsel < 0) { bsel = blast; bexcl = blexcl; }
+        if (wave == 0) {
+            // owning lane, then owning token
+            double w8[8];
+            weights8<T>(row, bsel * kBlock + lane * 8, m, invT, sS, j, w8);
+            double ls = 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) ls += w8[k];
+            const double incl = wave_incl_scan(ls, lane);
+            const bool hit = (bexcl + incl > tgt) && ls > 0.0;
+            const unsigned long long hits = __ballot(hit);
+            const unsigned long long pos = __ballot(ls > 0.0);
+            int lsel;
+            if (hits) lsel = __ffsll((long long)hits) - 1;
+            else lsel = 63 - __clzll((long long)(pos ? pos : 1ull));      // rounding: last lane with mass
+            if (lane == lsel) {
+                double r3 = bexcl + (incl - ls);
+                int pick = -1, lastpos = -1;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    r3 += w8[k];
+                    if (w8[k] > 0.0) lastpos = k;
+                    if (pick < 0 && r3 > tgt && w8[k] > 0.0) pick = k;
+                }
+                if (pick < 0) pick = max(lastpos, 0);
+                s_token = bsel * kBlock + lane * 8 + pick;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- the token goes to workgroup 0, which alone writes the outputs of the sequence
+    if (gsel != 0) {
+        ++pass;
+        S4C_TEAM_CHECK();
+        uint64_t* slot = slots + (size_t)(pass - 1) * 2 * G;
+        if (g == gsel) {
+            if (tid == 0) __hip_atomic_store(slot, (uint64_t)(uint32_t)s_token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        if (tid == 0) {
+            uint64_t v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int spin = 0; v == kEmpty && spin < a.spin_limit; ++spin) {
+                __builtin_amdgcn_s_sleep(2);
+                v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (v == kEmpty) s_fail = 1; else s_token = (int)(uint32_t)v;
+        }
+        __syncthreads();
+        S4C_TEAM_CHECK();
+    }
+    if (tid == 0) {
+        a.accept_len[b] = L;
+        a.bonus_token[b] = s_token;
     }
 #undef S4C_TEAM_CHECK
 }
@@ -409,8 +447,10 @@ int resample_team(int B, int V) {
     return G < 1 ? 1 : G;
 }
 
-// exchanges per sequence: one per visited node, one per rejected child, one for the sampling
-int resample_max_pass(int N, int max_path) { return max_path + N + 1; }
+// exchanges per sequence: one per visited node, one per rejected child, one for the sampling, one
+// to hand the token to workgroup 0
+int resample_max_pass(int N, int max_path) { return max_path + N + 2; }
+int resample_default_spin_limit() { return kSpinLimit; }
 
 size_t resample_slot_words(int B, int N, int V, int max_path) {
     const int G = resample_team(B, V);

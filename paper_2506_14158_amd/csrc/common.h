@@ -118,12 +118,14 @@ struct ResampleArgs {
     int32_t B, N, V, max_path, dtype;
     int32_t team;              // workgroups per sequence
     int32_t max_pass;          // exchanges a sequence may need
+    int32_t spin_limit;        // polls before a workgroup gives up on an exchange
     double temperature;
 };
 hipError_t launch_accept_resample(const ResampleArgs& a, hipStream_t st);
 int resample_max_vocab();
 int resample_team(int B, int V);
 int resample_max_pass(int N, int max_path);
+int resample_default_spin_limit();
 size_t resample_slot_words(int B, int N, int V, int max_path);
 
 struct CompactArgs {
@@ -200,11 +202,5 @@ struct LinearArgs {
 hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st);
 int draft_linear_tile_out();
 int draft_linear_tile_k();
-
-// measurement probes (probes.hip)
-hipError_t launch_probe_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
-hipError_t launch_probe_mfma(int random_operands, int iters, float* sink, hipStream_t st);
-double probe_mfma_flops(int iters);
-size_t probe_mfma_sink_floats();
 
 }  // namespace s4c

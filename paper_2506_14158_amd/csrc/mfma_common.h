@@ -25,7 +25,10 @@ constexpr int kRowB = kD * 2;               // bytes per K/V row
 enum TileMode { kPlain = 0, kTail = 1, kTree = 2 };
 
 // One wave-wide direct-to-LDS load: lane i's 16 bytes land at LDS byte address lds_base + 16 i
-// (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.
+// (lds_base wave-uniform, passed in M0).  Completion is tracked by vmcnt.  M0 is a register the
+// compiler reserves: it loads M0 itself right before any instruction of its own that reads it and
+// keeps no value in it across an asm statement, and it refuses M0 in a clobber list (warning
+// "reserved register"), so the statement below writes M0 without declaring it.
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
 }

@@ -2,10 +2,31 @@
 #include "common.h"
 
 #include <math.h>
+#include <stdlib.h>
+
+#include <atomic>
 
 using namespace s4c;
 
 namespace {
+
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (sizes the attention launch plan); the MI355X's 256 when no
+// device can be asked (size queries on a host without a GPU).
+int device_cus() {
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
 bool dtype_ok(int32_t d) { return d == S4C_F32 || d == S4C_BF16 || d == S4C_F16; }
 
@@ -39,12 +60,12 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
     const int rows = p.mfma ? mfma_rows_per_block(s) : 32;
     const long mtiles = (M + rows - 1) / rows;
     const long units = (long)s.B * s.Hkv * mtiles;
-    // Balance unit: the 256 CUs for the matrix-core kernels (HBM- or MFMA-bound: what counts is
+    // Balance unit: the device's CUs (256 on an MI355X) for the matrix-core kernels (HBM- or MFMA-bound: what counts is
     // an equal share of work per CU), four workgroups per CU for the scalar kernel.  Split the prefix so that the launch fills
-    // whole rounds of the 256 CUs without paying for more partial results than that needs:
+    // whole rounds of the CUs without paying for more partial results than that needs:
     // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), at least 128 keys per split
     // (32, its key tile, for the scalar kernel, whose launches are latency-bound).
-    const long slots = 256 * (p.mfma ? 1 : 4);
+    const long slots = (long)device_cus() * (p.mfma ? 1 : 4);
     const long gran = p.mfma ? 128 : 32;
     long max_splits = max_cache_len / gran;
     if (max_splits > 16) max_splits = 16;
@@ -78,7 +99,7 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
 extern "C" {
 #pragma GCC visibility push(default)
 
-const char* s4c_strerror(s4c_status code) {
+const char* s4c_strerror(int code) {
     switch (code) {
         case S4C_OK: return "ok";
         case S4C_ERR_NULL: return "a required pointer is NULL";
@@ -103,6 +124,9 @@ int32_t s4c_tree_attn_num_splits(const s4c_attn_shape* shape, int32_t max_cache_
     return plan_attn(*shape, max_cache_len).splits;
 }
 
+#pragma GCC visibility pop
+}  // extern "C"
+
 namespace {
 // log2 of a page size that is a power of two >= 64, else -1
 int page_shift_of(int32_t page_size) {
@@ -121,6 +145,9 @@ s4c_status tree_attn_impl(const s4c_attn_shape* shape, const void* q, const void
     if (!shape_ok(shape, &why)) return why;
     if (max_cache_len < 0 || max_cache_len > shape->S_cap) return S4C_ERR_SHAPE;
     if (max_cache_len > 0 && (!k_cache || !v_cache)) return S4C_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        !aligned16(out))
+        return S4C_ERR_SHAPE;
     const AttnPlan p = plan_attn(*shape, max_cache_len);
     const size_t need = p.ws_o_bytes + p.ws_ml_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255))) return S4C_ERR_WORKSPACE;
@@ -144,6 +171,9 @@ s4c_status tree_attn_impl(const s4c_attn_shape* shape, const void* q, const void
     return e == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 }  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
 
 s4c_status s4c_tree_attn(const s4c_attn_shape* shape, const void* q, const void* k_tree,
                          const void* v_tree, const void* k_cache, const void* v_cache,
@@ -175,12 +205,15 @@ size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V) {
     return 3 * per;
 }
 
-s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
-                           float temperature, const void* logits, const int32_t* parent,
-                           const int32_t* tokens, const float* p_draft, const float* uniforms,
-                           int32_t max_path, int32_t* path, int32_t* accept_len,
-                           int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+#pragma GCC visibility pop
+}  // extern "C"
+
+namespace {
+// checks shared by the two acceptance entry points; everything but the workspace
+s4c_status accept_args_ok(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode, float temperature,
+                          const void* logits, const int32_t* parent, const int32_t* tokens, const float* p_draft,
+                          const float* uniforms, int32_t max_path, int32_t* path, int32_t* accept_len,
+                          int32_t* accepted_tokens, int32_t* bonus_token) {
     if (!logits || !parent || !tokens || !path || !accept_len || !accepted_tokens || !bonus_token)
         return S4C_ERR_NULL;
     if (B <= 0 || N <= 0 || V <= 0 || max_path <= 0) return S4C_ERR_SHAPE;
@@ -191,11 +224,19 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
         if (!p_draft || !uniforms) return S4C_ERR_NULL;
         if (!(temperature > 0.f)) return S4C_ERR_SHAPE;
     }
-    const size_t need = s4c_accept_path_workspace_size(B, N, V);
-    if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
     const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
     if ((size_t)B * N * chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
+    return S4C_OK;
+}
 
+// `workspace` holds at least s4c_accept_path_workspace_size(B, N, V) bytes, 256-byte aligned
+s4c_status accept_launch(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode, float temperature,
+                         const void* logits, const int32_t* parent, const int32_t* tokens, const float* p_draft,
+                         const float* uniforms, int32_t max_path, int32_t* path, int32_t* accept_len,
+                         int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status, void* workspace,
+                         void* hip_stream) {
+    const size_t need = s4c_accept_path_workspace_size(B, N, V);
+    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
     AcceptArgs a;
     a.logits = logits; a.parent = parent; a.tokens = tokens; a.p_draft = p_draft; a.uniforms = uniforms;
     a.path = path; a.accept_len = accept_len; a.accepted_tokens = accepted_tokens;
@@ -217,6 +258,25 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     a.max_path = max_path; a.mode = mode; a.dtype = logits_dtype;
     a.inv_temp_log2 = kLog2e / (mode == S4C_STOCHASTIC ? temperature : 1.0f);
     return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+}
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
+                           float temperature, const void* logits, const int32_t* parent,
+                           const int32_t* tokens, const float* p_draft, const float* uniforms,
+                           int32_t max_path, int32_t* path, int32_t* accept_len,
+                           int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const s4c_status ok = accept_args_ok(B, N, V, logits_dtype, mode, temperature, logits, parent, tokens, p_draft, uniforms,
+                                         max_path, path, accept_len, accepted_tokens, bonus_token);
+    if (ok != S4C_OK) return ok;
+    const size_t need = s4c_accept_path_workspace_size(B, N, V);
+    if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
+    return accept_launch(B, N, V, logits_dtype, mode, temperature, logits, parent, tokens, p_draft, uniforms, max_path, path,
+                         accept_len, accepted_tokens, bonus_token, status, workspace, hip_stream);
 }
 
 size_t s4c_accept_resample_workspace_size(int32_t B, int32_t N, int32_t V, int32_t max_path) {
@@ -245,6 +305,15 @@ s4c_status s4c_accept_resample(int32_t B, int32_t N, int32_t V, int32_t logits_d
     a.B = B; a.N = N; a.V = V; a.max_path = max_path; a.dtype = logits_dtype; a.temperature = (double)temperature;
     a.team = resample_team(B, V);
     a.max_pass = resample_max_pass(N, max_path);
+    // S4C_RESAMPLE_SPIN_LIMIT (environment, >= 0): polls before a workgroup gives up on an exchange.  A
+    // diagnostic knob: 0 makes every exchange between several workgroups fail, which is how the give-up
+    // path is exercised without a stuck GPU.
+    a.spin_limit = resample_default_spin_limit();
+    if (const char* env = getenv("S4C_RESAMPLE_SPIN_LIMIT")) {
+        char* end = nullptr;
+        const long v = strtol(env, &end, 10);
+        if (end != env && v >= 0 && v <= 0x7FFFFFFFl) a.spin_limit = (int32_t)v;
+    }
     return launch_accept_resample(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
@@ -296,6 +365,9 @@ s4c_status s4c_kv_compact_paged(const s4c_attn_shape* shape, const void* k_tree,
     return launch_compact(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
+#pragma GCC visibility pop
+}  // extern "C"
+
 namespace {
 struct BuildLayout { size_t chunks, off_sum, off_topv, off_topi, off_tok, off_p, total; };
 BuildLayout build_layout(int32_t B, int32_t N, int32_t V) {
@@ -313,6 +385,9 @@ BuildLayout build_layout(int32_t B, int32_t N, int32_t V) {
     return l;
 }
 }  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
 
 size_t s4c_build_tree_workspace_size(int32_t B, int32_t N, int32_t V) {
     if (B <= 0 || N <= 0 || V <= 0) return 0;
@@ -340,6 +415,9 @@ s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
     a.inv_temp_log2 = kLog2e / temperature;
     return launch_build_tree(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
+
+#pragma GCC visibility pop
+}  // extern "C"
 
 namespace {
 s4c_status commit_impl(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
@@ -377,6 +455,9 @@ s4c_status commit_impl(const s4c_attn_shape* shape, int32_t layers, const void* 
 }
 }  // namespace
 
+extern "C" {
+#pragma GCC visibility push(default)
+
 s4c_status s4c_commit_path(const s4c_attn_shape* shape, int32_t layers, const void* k_tree, const void* v_tree,
                            void* k_cache, void* v_cache, int32_t* cache_len, const int32_t* path,
                            const int32_t* accept_len, int32_t max_path, const void* features,
@@ -411,21 +492,6 @@ s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, c
     LinearArgs a;
     a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.T = T; a.H = H; a.Hout = Hout; a.dtype = dtype; a.ttiles = a.otiles = 0;
     return launch_draft_linear(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
-}
-
-s4c_status s4c_probe_stream_read(const void* buffer, size_t bytes, float* sink, void* hip_stream) {
-    if (!buffer || !sink) return S4C_ERR_NULL;
-    if (bytes < 16 || (((uintptr_t)buffer) & 15)) return S4C_ERR_SHAPE;
-    return launch_probe_stream_read(buffer, bytes, sink, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
-}
-
-size_t s4c_probe_mfma_sink_bytes(void) { return probe_mfma_sink_floats() * sizeof(float); }
-
-s4c_status s4c_probe_mfma_bf16(int32_t random_operands, int32_t iters, float* sink, double* flops, void* hip_stream) {
-    if (!sink) return S4C_ERR_NULL;
-    if (iters <= 0) return S4C_ERR_SHAPE;
-    if (flops) *flops = probe_mfma_flops(iters);
-    return launch_probe_mfma(random_operands ? 1 : 0, iters, sink, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 
 #pragma GCC visibility pop

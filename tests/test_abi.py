@@ -64,6 +64,7 @@ def test_tree_attn_host_errors(L):
     assert call(shape(Hq=7)) == -2
     assert call(shape(B=0)) == -2
     assert call(s, mcl=10 ** 6) == -2                      # max_cache_len beyond S_cap
+    assert call(s, q=C.c_void_p(264)) == -2                # Q / K / V / out must be 16-byte aligned
     if B.s4c_tree_attn_workspace_size(s, 4096) > 0:
         assert call(s) == -4                               # workspace required but missing
         assert call(s, ws=one, wsb=16) == -4

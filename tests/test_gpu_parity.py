@@ -1,8 +1,8 @@
 """GPU-vs-oracle parity through the C ABI (needs an MI355X: run with -m gpu).
 
 Attention: element by element at sizes the oracle finishes in seconds (several tiles, ragged
-tails, odd shapes), and on sampled outputs at the full config sizes in the launch shape the
-benchmark times.  Tolerances: bf16 I/O with fp32 accumulation max abs <= 1e-2 and row-relative
+tails, odd shapes); at the full config sizes, in the launch shape the benchmark times, every
+output row of configs 2-4 and a sample of config 5 that hits every wavefront of the launch.  Tolerances: bf16 I/O with fp32 accumulation max abs <= 1e-2 and row-relative
 <= 2e-2; fp32 <= 1e-5.  Acceptance and compaction: bit-exact.
 """
 import numpy as np
@@ -209,9 +209,23 @@ def sample_triples(cfg, rng, n):
     return t
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5])
-def test_tree_attn_full_size_sampled(idx):
-    """Full config shape, benchmark launch configuration; the oracle evaluates sampled outputs."""
+def stratified_triples(cfg, rng, per_cell, rows_per_wave=32):
+    """(sequence, node, head) triples that hit every (sequence, KV head, query-row tile, wavefront) of
+    the launch: the M = N*G query rows of a KV head are dealt out in blocks of rows_per_wave to the
+    wavefronts of its workgroups; row r is node r // G, head kvh*G + r % G."""
+    G = cfg.Hq // cfg.Hkv
+    M = cfg.N * G
+    out = []
+    for b in range(cfg.B):
+        for kvh in range(cfg.Hkv):
+            for w0 in range(0, M, rows_per_wave):
+                rows = rng.choice(np.arange(w0, min(M, w0 + rows_per_wave)), size=per_cell, replace=False)
+                out += [(b, r // G, kvh * G + r % G) for r in rows]
+    out += [(0, 0, 0), (cfg.B - 1, cfg.N - 1, cfg.Hq - 1)]
+    return np.array(out, dtype=np.int32)
+
+
+def _full_size_run(idx):
     cfg = C[idx]
     par = synth.make_parent(cfg)
     at = synth.make_attn_inputs(cfg, threads=16)
@@ -222,14 +236,11 @@ def test_tree_attn_full_size_sampled(idx):
     torch.cuda.synchronize()
     out = tv.out.float().cpu().numpy()
     assert np.isfinite(out).all()
-    n = 96 if idx < 5 else 48
-    bnh = sample_triples(cfg, np.random.default_rng(idx), n)
-    ref = O.tree_attn_sampled(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par, bnh)
-    got = np.stack([out[b, i, h] for b, i, h in bnh]).astype(np.float64)
-    amax = np.abs(got - ref).max()
-    rel = (np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)).max()
-    print("cfg%d sampled: max abs %.3e rel %.3e splits %d" % (idx, amax, rel, tv.num_splits))
-    assert amax <= 1e-2 and rel <= 2e-2
+    assert tv.attn_status.cpu().tolist() == [0] * cfg.B
+    return cfg, par, at, d, tv, out
+
+
+def _root_rows_ignore_other_nodes(d, tv):
     # property that holds at any size: the root row of every head only sees prefix + itself, so it
     # must not change when every other tree node's K/V is scrambled
     kt2 = d["k_tree"].clone()
@@ -238,6 +249,59 @@ def test_tree_attn_full_size_sampled(idx):
     tv.tree_attn(d["q"], kt2, d["v_tree"], d["k_cache"], d["v_cache"], d["cache_len"], d["parent"])
     torch.cuda.synchronize()
     assert torch.equal(tv.out[:, 0].view(torch.int16), root_before.view(torch.int16))
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_tree_attn_full_size_every_row(idx):
+    """Configs 2-4 at full size in the launch configuration the benchmark times: EVERY output row
+    (1920 / 10240 / 16384 rows of 128) against the oracle."""
+    cfg, par, at, d, tv, out = _full_size_run(idx)
+    ref, st = O.tree_attn(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par)
+    assert (st == 0).all()
+    amax, rel = attn_errors(tv.out, ref)
+    print("cfg%d all %d rows: max abs %.3e rel %.3e splits %d" % (idx, cfg.B * cfg.N * cfg.Hq, amax, rel, tv.num_splits))
+    assert amax <= TOL["bf16"][0] and rel <= TOL["bf16"][1]
+    _root_rows_ignore_other_nodes(d, tv)
+
+
+def test_tree_attn_full_size_cfg5_stratified():
+    """Config 5 at full size (131072 output rows; the oracle does ~700 of them per second): two rows
+    from every (sequence, KV head, row tile, wavefront) of the 512-workgroup launch, 8194 rows."""
+    cfg, par, at, d, tv, out = _full_size_run(5)
+    bnh = stratified_triples(cfg, np.random.default_rng(5), per_cell=2)
+    assert len(bnh) == cfg.B * cfg.Hkv * (cfg.N * cfg.G // 32) * 2 + 2
+    ref = O.tree_attn_sampled(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par, bnh)
+    got = out[bnh[:, 0], bnh[:, 1], bnh[:, 2]].astype(np.float64)
+    amax = np.abs(got - ref).max()
+    rel = (np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)).max()
+    print("cfg5 stratified %d rows: max abs %.3e rel %.3e splits %d" % (len(bnh), amax, rel, tv.num_splits))
+    assert amax <= 1e-2 and rel <= 2e-2
+    _root_rows_ignore_other_nodes(d, tv)
+
+
+def bf16_rne(x64):
+    """float64 -> nearest bf16 value (ties to even), as float64."""
+    return synth.as_f32(synth.f32_to_bf16_bits(x64.astype(np.float32)), "bf16").astype(np.float64)
+
+
+def test_tree_attn_large_outputs_need_the_ulp_aware_bar():
+    """Empty prefix, 122 nodes, 16 heads per KV head, N(0,1) values: a node attends to a handful of
+    ancestors, so some outputs have magnitude 2..4, where the bf16 output's own half-ulp (2^-8 |o|
+    rounded up to the binade: 0.0078) already uses up most of a fixed 1e-2 bar; this shape class
+    measured max |g - o| = 0.0103.  The bar here is the ulp-aware one, and the claim that the excess
+    is the output's storage rounding is checked directly: wherever |o| >= 1 the kernel's bf16 output
+    is within one bf16 ulp of the correctly rounded oracle value."""
+    cfg = synth.scaled(C[4], name="p0-n122-g16", B=4, Hq=48, Hkv=3, D=128, dtype="bf16", P=0, N=122, levels=7,
+                       widths=(8, 4, 3, 2, 2, 2, 2, 2, 2), index=0)
+    tv, d, amax, rel = check_attn_full(cfg, ulp_aware=True)
+    at, par = synth.make_attn_inputs(cfg), synth.make_parent(cfg)
+    ref, _ = O.tree_attn(at.q, at.k_tree, at.v_tree, at.k_cache, at.v_cache, at.cache_len, par)
+    g = tv.out.float().cpu().numpy().astype(np.float64)
+    big = np.abs(ref) >= 1.0
+    assert big.sum() > 1000 and np.abs(ref).max() > 2.0          # the shape does produce such outputs
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(ref[big]))) - 7)
+    assert (np.abs(g[big] - bf16_rne(ref[big])) <= ulp).all()
+    print(cfg.name, "max abs %.3e rel %.3e, %d outputs with |o| >= 1, largest %.2f" % (amax, rel, big.sum(), np.abs(ref).max()))
 
 
 # ------------------------------------------------------------------------------ acceptance
@@ -369,7 +433,7 @@ def test_whole_step_bit_exact_cache(cfg):
     assert amax <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1]
 
 
-@pytest.mark.parametrize("idx", [3, 4, 5])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_kv_compact_full_size(idx):
     """The named configs at full size: the oracle's accepted paths appended by the GPU; destination
     rows, cache_len and every byte of both caches (appended rows and everything else) checked."""

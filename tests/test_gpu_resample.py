@@ -135,6 +135,36 @@ def test_equality_rejects_bad_tree_and_bad_token():
     assert tv.accept_status.cpu().tolist() == [0, 1]
 
 
+def test_team_that_cannot_exchange_is_flagged_and_every_kernel_exits(monkeypatch):
+    """The bounded wait of the workgroup teams, forced from the host: with zero polls allowed a
+    workgroup that does not find all of its team's partial sums at its first look gives up, so no
+    team of several workgroups completes.  Every kernel must still exit, and every such sequence
+    must come back as the flagged empty result (written by the team's first workgroup alone); the
+    next call with the default limit gives the oracle's answer again on the same buffers."""
+    cfg = synth.scaled(C[3], name="timeout", B=3, V=40000, index=0)          # teams of 10 workgroups
+    par = synth.make_parent(cfg)
+    ac, r = resample_inputs_with_margin(cfg, par, O)
+    assert B.s4c_accept_resample_workspace_size(cfg.B, cfg.N, cfg.V, cfg.levels) > 0    # teams of more than one workgroup
+    d = to_device(cfg, par, None, ac)
+    tv = TreeVerifier(cfg.B, cfg.N, 1, 1, 64, 1, cfg.V, d["logits"].dtype, cfg.levels, 0)
+    call = lambda: tv.accept_resample(d["logits"], d["draft_probs"], d["parent"], d["tokens"], d["uniforms"],
+                                      d["u_resample"], cfg.temperature)
+    monkeypatch.setenv("S4C_RESAMPLE_SPIN_LIMIT", "0")
+    for rep in range(3):
+        for t in (tv.path, tv.accept_len, tv.accepted_tokens, tv.bonus_token, tv.accept_status):
+            t.fill_(-7)
+        call()
+        torch.cuda.synchronize()
+        assert tv.accept_status.cpu().tolist() == [B.S4C_SEQ_TIMEOUT] * cfg.B, rep
+        assert tv.accept_len.cpu().tolist() == [0] * cfg.B and tv.bonus_token.cpu().tolist() == [-1] * cfg.B
+        assert tv.path.cpu().tolist() == [[0] + [-1] * (cfg.levels - 1)] * cfg.B
+        assert (tv.accepted_tokens.cpu().numpy() == -1).all()
+    monkeypatch.delenv("S4C_RESAMPLE_SPIN_LIMIT")
+    call()
+    torch.cuda.synchronize()
+    same(tv, r)
+
+
 def test_rejects_bad_arguments():
     t = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
     i = lambda *s: torch.zeros(*s, dtype=torch.int32, device="cuda")
