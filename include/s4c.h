@@ -12,8 +12,8 @@
  * Conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller; `shape` structs are HOST
  *     pointers.  The library allocates nothing.  What it keeps between calls is per-GPU set-up
- *     only: which of its kernels already had their dynamic-LDS limit raised and the compute-unit
- *     count it sizes launches by.
+ *     only: which of its kernels already had their dynamic-LDS limit raised, the compute-unit
+ *     count it sizes launches by, and the address of the fixed scratch of s4c_accept_path_static.
  *   - Q, K, V, the caches / pools and `out` must be 16-byte aligned (checked: S4C_ERR_SHAPE);
  *     logits rows may have any alignment.  Floating-point inputs must be finite (no NaN, no
  *     infinity): the kernels are compiled without NaN handling, and a non-finite input gives an
@@ -45,7 +45,8 @@ typedef enum {
     S4C_ERR_SHAPE = -2,        /* non-positive or inconsistent sizes */
     S4C_ERR_UNSUPPORTED = -3,  /* N > 128, D not in {64,128}, unknown dtype or mode */
     S4C_ERR_WORKSPACE = -4,    /* workspace missing or smaller than *_workspace_size() */
-    S4C_ERR_HIP = -5           /* kernel launch failed (hipGetLastError) */
+    S4C_ERR_HIP = -5,          /* kernel launch failed (hipGetLastError) */
+    S4C_ERR_STATIC_SCRATCH = -6 /* s4c_accept_path_static: the problem needs more than S4C_STATIC_SCRATCH_BYTES */
 } s4c_status;
 
 typedef enum { S4C_F32 = 0, S4C_BF16 = 1, S4C_F16 = 2 } s4c_dtype;
@@ -138,6 +139,25 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
                            int32_t max_path, int32_t* path, int32_t* accept_len,
                            int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* s4c_accept_path for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments minus
+ * the workspace, same results.  The per-row partial statistics go to a fixed scratch array that
+ * lives in the library's device image (S4C_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends); the call allocates nothing.  Problems with
+ * s4c_accept_path_workspace_size(B, N, V) > S4C_STATIC_SCRATCH_BYTES are refused with
+ * S4C_ERR_STATIC_SCRATCH (1 MiB covers B*N*ceil(V/8192) <= 87381; 2048 rows of 128256 logits need
+ * 384 KB).  All calls on one GPU share that GPU's array: two calls that may overlap in
+ * time on one GPU (different streams) race, calls on one stream do not.  The array's device address
+ * is looked up on the first call on each GPU (hipGetSymbolAddress, no allocation); make that first
+ * call outside a graph capture. */
+#define S4C_STATIC_SCRATCH_BYTES (1 << 20)
+s4c_status s4c_accept_path_static(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
+                                  float temperature, const void* logits, const int32_t* parent,
+                                  const int32_t* tokens, const float* p_draft, const float* uniforms,
+                                  int32_t max_path, int32_t* path, int32_t* accept_len,
+                                  int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                                  void* hip_stream);
 
 /* Sibling-sequential acceptance with the correction token (Sec. 2, speculative-sampling
  * paragraph: accept with probability min(1, p/q), redraw a rejected token from

@@ -21,7 +21,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN, S4C_SEQ_TIMEOUT = 1, 2, 4
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged")
+           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged", "s4c_accept_path_static")
 
 
 class S4CError(RuntimeError):
@@ -84,6 +84,9 @@ def lib() -> C.CDLL:
             C.c_int32] + [C.c_void_p] * 3
         L.s4c_draft_linear.restype = C.c_int
         L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6
+        L.s4c_accept_path_static.restype = C.c_int
+        L.s4c_accept_path_static.argtypes = [C.c_int32] * 5 + [C.c_float] + [C.c_void_p] * 5 + [C.c_int32] + [
+            C.c_void_p] * 6
         L.s4c_strerror.restype = C.c_char_p
         L.s4c_strerror.argtypes = [C.c_int]
         _lib = L
@@ -228,6 +231,20 @@ def s4c_accept_path(logits, parent, tokens, mode: int, max_path: int, path, acce
                                  _ptr(parent), _ptr(tokens), _ptr(p_draft), _ptr(uniforms), int(max_path),
                                  _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
                                  _ptr(status), _ptr(workspace), ws_bytes, _stream()))
+
+
+S4C_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def s4c_accept_path_static(logits, parent, tokens, mode: int, max_path: int, path, accept_len, accepted_tokens,
+                           bonus_token, p_draft=None, uniforms=None, temperature: float = 1.0,
+                           status: Optional[torch.Tensor] = None) -> None:
+    """s4c_accept_path without a workspace argument: the library's fixed per-GPU scratch is used."""
+    B, N, V = _accept_checks(logits, parent, tokens, max_path, path, accept_len, accepted_tokens, bonus_token, p_draft, uniforms)
+    _check(lib().s4c_accept_path_static(B, N, V, _dtype_code(logits), int(mode), float(temperature), _ptr(logits),
+                                        _ptr(parent), _ptr(tokens), _ptr(p_draft), _ptr(uniforms), int(max_path),
+                                        _ptr(path), _ptr(accept_len), _ptr(accepted_tokens), _ptr(bonus_token),
+                                        _ptr(status), _stream()))
 
 
 def s4c_accept_resample_workspace_size(B: int, N: int, V: int, max_path: int) -> int:

@@ -8,6 +8,11 @@
 
 using namespace s4c;
 
+// Scratch of s4c_accept_path_static: one copy per GPU that loads the library, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address of each
+// GPU's copy is looked up once per device (static_scratch) and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char scratch[S4C_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kMaxDevices = 64;
@@ -24,6 +29,24 @@ int device_cus() {
         cached[dev].store(n, std::memory_order_relaxed);
     }
     return n;
+}
+
+// Device address of the current GPU's copy of `scratch`.
+hipError_t static_scratch(void** out) {
+    static std::atomic<void*> addr[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
 }
 
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -107,6 +130,7 @@ const char* s4c_strerror(int code) {
         case S4C_ERR_UNSUPPORTED: return "unsupported size, dtype or mode (N <= 128, D in {64,128})";
         case S4C_ERR_WORKSPACE: return "workspace missing or too small";
         case S4C_ERR_HIP: return "HIP kernel launch failed";
+        case S4C_ERR_STATIC_SCRATCH: return "problem larger than the static scratch of s4c_accept_path_static";
     }
     return "unknown status";
 }
@@ -277,6 +301,22 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
     if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
     return accept_launch(B, N, V, logits_dtype, mode, temperature, logits, parent, tokens, p_draft, uniforms, max_path, path,
                          accept_len, accepted_tokens, bonus_token, status, workspace, hip_stream);
+}
+
+s4c_status s4c_accept_path_static(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
+                                  float temperature, const void* logits, const int32_t* parent,
+                                  const int32_t* tokens, const float* p_draft, const float* uniforms,
+                                  int32_t max_path, int32_t* path, int32_t* accept_len,
+                                  int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status,
+                                  void* hip_stream) {
+    const s4c_status ok = accept_args_ok(B, N, V, logits_dtype, mode, temperature, logits, parent, tokens, p_draft, uniforms,
+                                         max_path, path, accept_len, accepted_tokens, bonus_token);
+    if (ok != S4C_OK) return ok;
+    if (s4c_accept_path_workspace_size(B, N, V) > (size_t)S4C_STATIC_SCRATCH_BYTES) return S4C_ERR_STATIC_SCRATCH;
+    void* ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return S4C_ERR_HIP;
+    return accept_launch(B, N, V, logits_dtype, mode, temperature, logits, parent, tokens, p_draft, uniforms, max_path, path,
+                         accept_len, accepted_tokens, bonus_token, status, ws, hip_stream);
 }
 
 size_t s4c_accept_resample_workspace_size(int32_t B, int32_t N, int32_t V, int32_t max_path) {
