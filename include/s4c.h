@@ -55,9 +55,9 @@ typedef enum { S4C_GREEDY = 0, S4C_STOCHASTIC = 1 } s4c_accept_mode;
 /* bits of the per-sequence device status word */
 #define S4C_SEQ_BAD_TREE 1     /* parent[] is not a valid tree / path deeper than max_path */
 #define S4C_SEQ_BAD_LEN  2     /* cache_len out of range / accepted rows do not fit S_cap */
-#define S4C_SEQ_TIMEOUT  4     /* s4c_accept_resample: the workgroups of a sequence could not exchange
-                                  their partial sums within the poll limit (GPU shared with a kernel
-                                  that never ends); accept_len = 0, path = [0], bonus = -1 */
+#define S4C_SEQ_TIMEOUT  4     /* s4c_accept_path, s4c_accept_resample: the workgroups of a sequence could not
+                                  hand their partial results to each other within the waiting limit (a GPU
+                                  that stopped scheduling them); accept_len = 0, path = [0], bonus = -1 */
 
 typedef struct {
     int32_t B;       /* sequences */
@@ -109,7 +109,9 @@ s4c_status s4c_tree_attn_paged(const s4c_attn_shape* shape, const void* q, const
                                const int32_t* parent, int32_t max_cache_len, float scale, void* out,
                                int32_t* status, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Bytes of device workspace s4c_accept_path needs (per-row partial statistics). */
+/* Bytes of device workspace s4c_accept_path needs (per-row partial statistics).  Its contents need not be
+ * initialised and may be anything a previous call left there; two calls that may overlap in time must
+ * not share it. */
 size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V);
 
 /* Acceptance and longest accepted path (Sec. 3.2).
@@ -130,7 +132,13 @@ size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V);
  *   accepted_tokens [B][max_path] tokens of path[1..], -1 padded
  *   bonus_token     [B] greedy: argmax of the last path node's row; stochastic: -1
  *   status          [B] nullable; S4C_SEQ_BAD_TREE if parent[] is malformed or a node is deeper
- *                   than max_path-1: then accept_len = 0, path = [0], bonus = -1.
+ *                   than max_path-1: then accept_len = 0, path = [0], bonus = -1.  S4C_SEQ_TIMEOUT
+ *                   (same result) if the sequence's partial statistics did not all reach its
+ *                   collecting workgroup within 2 s -- one launch does the scan and the path step,
+ *                   and that wait is bounded so that every kernel ends.  The environment variable
+ *                   S4C_ACCEPT_WAIT_US (an integer >= 0, read at every call) replaces the 2 s; 0
+ *                   makes a collector that has to wait give up at once, which exercises the
+ *                   flagged path on a healthy GPU.
  * Softmax statistics are fp32.  In STOCHASTIC mode the logits rows of leaf nodes are never read (they
  * verify no node and that mode returns no bonus token); in GREEDY mode every row may be read. */
 s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, int32_t mode,
@@ -146,8 +154,8 @@ s4c_status s4c_accept_path(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
  * lives in the library's device image (S4C_STATIC_SCRATCH_BYTES per GPU, held until the process
  * ends); the call allocates nothing.  Problems with
  * s4c_accept_path_workspace_size(B, N, V) > S4C_STATIC_SCRATCH_BYTES are refused with
- * S4C_ERR_STATIC_SCRATCH (1 MiB covers B*N*ceil(V/8192) <= 87381; 2048 rows of 128256 logits need
- * 384 KB).  All calls on one GPU share that GPU's array: two calls that may overlap in
+ * S4C_ERR_STATIC_SCRATCH (1 MiB covers 43690 row segments of up to 65536 logits; 2048 rows of 128256
+ * logits are 4096 segments, 96 KB).  All calls on one GPU share that GPU's array: two calls that may overlap in
  * time on one GPU (different streams) race, calls on one stream do not.  The array's device address
  * is looked up on the first call on each GPU (hipGetSymbolAddress, no allocation); make that first
  * call outside a graph capture. */

@@ -92,15 +92,16 @@ struct AcceptArgs {
     int32_t* accepted_tokens;
     int32_t* bonus_token;
     int32_t* status;
-    float* ws_max;     // [B*N][nseg]
-    int32_t* ws_arg;   // [B*N][nseg]
-    float* ws_sum;     // [B*N][nseg]
+    unsigned long long* rec;   // [B*N][nseg][3] (call nonce << 32) | bits of (max, argmax, sum of exponentials)
+    uint32_t nonce;    // tells this call's records from whatever the words held before
+    long long wait_ticks;   // how long a collector waits for its sequence's records (100 MHz wall clock)
     int32_t B, N, V, chunks, max_path, mode, dtype;
     int32_t seg, nseg; // chunks per workgroup, workgroups per row
     float inv_temp_log2;   // log2(e) / T
 };
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
 int accept_chunk_elems();
+void accept_plan(int B, int N, int V, int* chunks, int* seg, int* nseg);
 
 struct ResampleArgs {
     const void* logits;

@@ -51,6 +51,18 @@ hipError_t static_scratch(void** out) {
 
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
+// A different number for every acceptance call of the process (the records of a workspace tell this
+// call's statistics from older contents by it).  Never 0 or ~0: freshly allocated memory is often all
+// zeros, which must read as "no record yet", and ~nonce marks a consumed record.
+uint32_t next_nonce() {
+    static std::atomic<uint32_t> counter{0};
+    for (;;) {
+        uint32_t x = counter.fetch_add(1, std::memory_order_relaxed) + 0x9E3779B9u;
+        x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;      // a bijection of 32-bit words
+        if (x != 0u && x != 0xFFFFFFFFu) return x;
+    }
+}
+
 bool dtype_ok(int32_t d) { return d == S4C_F32 || d == S4C_BF16 || d == S4C_F16; }
 
 bool shape_ok(const s4c_attn_shape* s, s4c_status* why) {
@@ -224,9 +236,9 @@ s4c_status s4c_tree_attn_paged(const s4c_attn_shape* shape, const void* q, const
 
 size_t s4c_accept_path_workspace_size(int32_t B, int32_t N, int32_t V) {
     if (B <= 0 || N <= 0 || V <= 0) return 0;
-    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
-    const size_t per = (((size_t)B * N * chunks * 4 + 255) / 256) * 256;
-    return 3 * per;
+    int chunks, seg, nseg;
+    accept_plan(B, N, V, &chunks, &seg, &nseg);
+    return (((size_t)B * N * nseg * 3 * sizeof(unsigned long long) + 255) / 256) * 256;   // three records per (row, segment)
 }
 
 #pragma GCC visibility pop
@@ -248,8 +260,9 @@ s4c_status accept_args_ok(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
         if (!p_draft || !uniforms) return S4C_ERR_NULL;
         if (!(temperature > 0.f)) return S4C_ERR_SHAPE;
     }
-    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
-    if ((size_t)B * N * chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
+    int chunks, seg, nseg;
+    accept_plan(B, N, V, &chunks, &seg, &nseg);
+    if ((size_t)B * N * nseg > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
     return S4C_OK;
 }
 
@@ -259,26 +272,24 @@ s4c_status accept_launch(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, 
                          const float* uniforms, int32_t max_path, int32_t* path, int32_t* accept_len,
                          int32_t* accepted_tokens, int32_t* bonus_token, int32_t* status, void* workspace,
                          void* hip_stream) {
-    const size_t need = s4c_accept_path_workspace_size(B, N, V);
-    const size_t chunks = ((size_t)V + accept_chunk_elems() - 1) / accept_chunk_elems();
     AcceptArgs a;
     a.logits = logits; a.parent = parent; a.tokens = tokens; a.p_draft = p_draft; a.uniforms = uniforms;
     a.path = path; a.accept_len = accept_len; a.accepted_tokens = accepted_tokens;
     a.bonus_token = bonus_token; a.status = status;
-    const size_t per = need / 3;
-    a.ws_max = (float*)workspace;
-    a.ws_arg = (int32_t*)((char*)workspace + per);
-    a.ws_sum = (float*)((char*)workspace + 2 * per);
-    a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)chunks;
-    // Segment length: up to about 8192 workgroups per launch, but at least two chunks per workgroup
-    // (so the second streams in while the first is reduced) once there are 4096 chunks to hand out.
-    const size_t units = (size_t)B * N * chunks;
-    size_t seg = (units + 8191) / 8192;
-    if (seg < 2 && units >= 4096) seg = 2;
-    if (seg < 1) seg = 1;
-    if (seg > chunks) seg = chunks;
-    a.seg = (int32_t)seg;
-    a.nseg = (int32_t)((chunks + seg - 1) / seg);
+    a.rec = (unsigned long long*)workspace;
+    a.nonce = next_nonce();
+    // S4C_ACCEPT_WAIT_US (environment, >= 0): how long a sequence's collecting workgroup waits for the
+    // statistics of the others before it flags the sequence.  A diagnostic knob: 0 makes a collector that
+    // does not find everything at its first look give up, which exercises the flagged path on a healthy GPU.
+    long long wait_us = 2000000;
+    if (const char* env = getenv("S4C_ACCEPT_WAIT_US")) {
+        char* end = nullptr;
+        const long long v = strtoll(env, &end, 10);
+        if (end != env && v >= 0 && v <= 60000000ll) wait_us = v;
+    }
+    a.wait_ticks = wait_us * 100;
+    a.B = B; a.N = N; a.V = V;
+    accept_plan(B, N, V, &a.chunks, &a.seg, &a.nseg);
     a.max_path = max_path; a.mode = mode; a.dtype = logits_dtype;
     a.inv_temp_log2 = kLog2e / (mode == S4C_STOCHASTIC ? temperature : 1.0f);
     return launch_accept(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;

@@ -88,8 +88,8 @@ def test_accept_and_compact_host_errors(L):
     st = lambda Bn=2, N=8, V=100, mode=0, logits=one, pd=one: \
         L.s4c_accept_path_static(Bn, N, V, 1, mode, 1.0, logits, one, one, pd, one, 4, one, one, one, one, None, None)
     assert st(logits=None) == -1 and st(N=129) == -3 and st(V=0) == -2 and st(mode=1, pd=None) == -1
-    assert B.s4c_accept_path_workspace_size(16, 128, 800000) > B.S4C_STATIC_SCRATCH_BYTES
-    assert st(Bn=16, N=128, V=800000) == -6 and "static scratch" in B.s4c_strerror(-6)
+    assert B.s4c_accept_path_workspace_size(16, 128, 2000000) > B.S4C_STATIC_SCRATCH_BYTES
+    assert st(Bn=16, N=128, V=2000000) == -6 and "static scratch" in B.s4c_strerror(-6)
     s = shape()
     cmp_ = lambda sh=s, kt=one, mp=4: L.s4c_kv_compact(C.byref(sh), kt, one, one, one, one, one, one, mp, None, None, None)
     assert cmp_(kt=None) == -1

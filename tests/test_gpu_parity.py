@@ -373,6 +373,66 @@ def test_stochastic_acceptance_never_reads_leaf_rows():
     assert (tv.bonus_token.cpu().numpy() == -1).all()
 
 
+def test_accept_repeated_calls_need_no_workspace_initialisation():
+    """The acceptance workspace carries per-call tags instead of counters that would have to start at
+    zero: the same answer must come out of many calls in a row, whatever the workspace held before each
+    (zeros, the previous call's leftovers, random bytes), in both modes."""
+    for cfg in (synth.scaled(C[1], name="rep-greedy", V=1003, B=3, index=0),
+                synth.scaled(C[3], name="rep-stochastic", B=2, V=9000, index=0)):
+        par = synth.make_parent(cfg)
+        ac, r = accept_inputs_with_margin(cfg, par, O)
+        d = to_device(cfg, par, None, ac)
+        tv = verifier(cfg, d)
+        mode = B.S4C_GREEDY if cfg.mode == "greedy" else B.S4C_STOCHASTIC
+        g = torch.Generator(device="cuda").manual_seed(11)
+        for it in range(12):
+            if it % 3 == 0:
+                tv.accept_ws.zero_()
+            elif it % 3 == 1:
+                tv.accept_ws.copy_(torch.randint(0, 256, tv.accept_ws.shape, device="cuda", generator=g, dtype=torch.int32).to(torch.uint8))
+            for t in (tv.path, tv.accept_len, tv.accepted_tokens, tv.bonus_token, tv.accept_status):
+                t.fill_(-7)
+            tv.accept_path(d["logits"], d["parent"], d["tokens"], mode, d["p_draft"], d["uniforms"], cfg.temperature)
+            torch.cuda.synchronize()
+            assert np.array_equal(tv.accept_status.cpu().numpy(), r["status"]), (cfg.name, it)
+            assert np.array_equal(tv.path.cpu().numpy(), r["path"]), (cfg.name, it)
+            assert np.array_equal(tv.accept_len.cpu().numpy(), r["accept_len"]), (cfg.name, it)
+            assert np.array_equal(tv.bonus_token.cpu().numpy(), r["bonus_token"]), (cfg.name, it)
+
+
+def test_accept_collector_that_gives_up_flags_the_sequence(monkeypatch):
+    """The bounded wait of the collecting workgroups, forced from the host: with a waiting time of zero a
+    collector that does not find all of its sequence's statistics at its first look gives up.  The launch
+    below has more scanning workgroups than fit on the GPU at once, and the collectors (which have no
+    segment of their own in stochastic mode) are the last of the grid, so they start while the last
+    scanning workgroups have only just begun 128 KB segments.  Every kernel must exit, the sequences
+    must come back flagged and empty, and the next call with the default wait must give the oracle's
+    answer on the same buffers."""
+    cfg = synth.scaled(C[3], name="accept-timeout", B=2, V=1_000_003, index=0)
+    par = synth.make_parent(cfg)
+    ac, r = accept_inputs_with_margin(cfg, par, O)
+    d = to_device(cfg, par, None, ac)
+    tv = verifier(cfg, d)
+    call = lambda: tv.accept_path(d["logits"], d["parent"], d["tokens"], B.S4C_STOCHASTIC, d["p_draft"], d["uniforms"],
+                                  cfg.temperature)
+    monkeypatch.setenv("S4C_ACCEPT_WAIT_US", "0")
+    for rep in range(2):
+        for t in (tv.path, tv.accept_len, tv.accepted_tokens, tv.bonus_token, tv.accept_status):
+            t.fill_(-7)
+        call()
+        torch.cuda.synchronize()
+        assert tv.accept_status.cpu().tolist() == [B.S4C_SEQ_TIMEOUT] * cfg.B, rep
+        assert tv.accept_len.cpu().tolist() == [0] * cfg.B and tv.bonus_token.cpu().tolist() == [-1] * cfg.B
+        assert tv.path.cpu().tolist() == [[0] + [-1] * (cfg.levels - 1)] * cfg.B
+        assert (tv.accepted_tokens.cpu().numpy() == -1).all()
+    monkeypatch.delenv("S4C_ACCEPT_WAIT_US")
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(tv.accept_status.cpu().numpy(), r["status"])
+    assert np.array_equal(tv.path.cpu().numpy(), r["path"])
+    assert np.array_equal(tv.accept_len.cpu().numpy(), r["accept_len"])
+
+
 def test_accept_argmax_ties_and_hand_example():
     """bf16 logits tie often; the lowest token id must win on the GPU exactly as in the oracle."""
     rng = np.random.default_rng(3)
