@@ -162,6 +162,7 @@ struct BuildArgs {
     int32_t* row_tok;          // [B*N][8]
     float* row_p;              // [B*N][8]
     int32_t B, N, V, chunks, kmax, dtype;
+    int32_t seg, nseg;         // chunks per workgroup of the scan, workgroups per row
     float inv_temp_log2;
 };
 hipError_t launch_build_tree(const BuildArgs& a, hipStream_t st);

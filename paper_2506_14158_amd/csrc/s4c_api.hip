@@ -427,10 +427,11 @@ BuildLayout build_layout(int32_t B, int32_t N, int32_t V) {
     const size_t rows = (size_t)B * N, K = (size_t)build_tree_max_children();
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     size_t o = 0;
-    o += up(rows * l.chunks * 4); l.off_sum = o;
-    o += up(rows * l.chunks * 4); l.off_topv = o;
-    o += up(rows * l.chunks * K * 4); l.off_topi = o;
-    o += up(rows * l.chunks * K * 4); l.off_tok = o;
+    const size_t parts = l.chunks * 4;            // every wavefront of the scan reports its quarter of a chunk
+    o += up(rows * parts * 4); l.off_sum = o;
+    o += up(rows * parts * 4); l.off_topv = o;
+    o += up(rows * parts * K * 4); l.off_topi = o;
+    o += up(rows * parts * K * 4); l.off_tok = o;
     o += up(rows * K * 4); l.off_p = o;
     o += up(rows * K * 4); l.total = o;
     return l;
@@ -454,7 +455,7 @@ s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
     if (N > kMaxNodes || kmax > build_tree_max_children() || !dtype_ok(logits_dtype))
         return S4C_ERR_UNSUPPORTED;
     const BuildLayout l = build_layout(B, N, V);
-    if ((size_t)B * N * l.chunks > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
+    if ((size_t)B * N * l.chunks * 4 * (size_t)build_tree_max_children() > 0x7FFFFFFFull) return S4C_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < l.total || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
     BuildArgs a;
     a.logits = draft_logits; a.nchild = nchild; a.root_token = root_token; a.parent = parent; a.tokens = tokens;
@@ -463,6 +464,10 @@ s4c_status s4c_build_tree(int32_t B, int32_t N, int32_t V, int32_t logits_dtype,
     a.ws_max = (float*)w; a.ws_sum = (float*)(w + l.off_sum); a.ws_topv = (float*)(w + l.off_topv);
     a.ws_topi = (int32_t*)(w + l.off_topi); a.row_tok = (int32_t*)(w + l.off_tok); a.row_p = (float*)(w + l.off_p);
     a.B = B; a.N = N; a.V = V; a.chunks = (int32_t)l.chunks; a.kmax = kmax; a.dtype = logits_dtype;
+    {   // segments as in the acceptance scan (same chunk size, same sizes of launch)
+        int chunks_ = 0;
+        accept_plan(B, N, V, &chunks_, &a.seg, &a.nseg);
+    }
     a.inv_temp_log2 = kLog2e / temperature;
     return launch_build_tree(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
