@@ -403,20 +403,28 @@ def main():
         del kp, vp
     if args.draft_linear and cfg.dtype != "f32":
         dt_ = d0["q"].dtype
-        Tn, Hd = cfg.B * cfg.N, cfg.Hq * cfg.D
+        Hd = cfg.Hq * cfg.D
         g = torch.Generator(device="cuda").manual_seed(1)
         rn = lambda *s_: torch.randn(*s_, device="cuda", generator=g)
-        e_, f_ = rn(Tn, Hd).to(dt_), rn(Tn, Hd).to(dt_)
         W_ = (rn(Hd, 2 * Hd) / (2 * Hd) ** 0.5).to(dt_)
         b_ = rn(Hd).to(dt_)
-        o_ = torch.empty(Tn, Hd, dtype=dt_, device="cuda")
-        t_dl, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: B.s4c_draft_linear(e_, f_, W_, o_, b_)))
-        t_lib, _ = (lambda fn: (min(fn() for _ in range(5)), None))(lambda: _timed_ms(torch, lambda: torch.addmm(b_, torch.cat([e_, f_], 1), W_.t())))
-        fl = 2.0 * Tn * 2 * Hd * Hd
-        rec["draft_linear"] = {"tokens": Tn, "hidden": Hd, "ms": t_dl, "TFLOPs": fl / t_dl / 1e9,
-                               "frac_of_mfma_peak": fl / t_dl / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                               "torch_cat_addmm_ms": t_lib, "torch_TFLOPs": fl / t_lib / 1e9}
-        del e_, f_, W_, o_
+        best = lambda fn: min(_timed_ms(torch, fn) for _ in range(5))
+        rec["draft_linear"] = []
+        # the batch's B*N tree tokens (a dense contraction), and one tree's N tokens (<= 128: a stream over W)
+        for Tn in (cfg.B * cfg.N, cfg.N):
+            e_, f_ = rn(Tn, Hd).to(dt_), rn(Tn, Hd).to(dt_)
+            o_ = torch.empty(Tn, Hd, dtype=dt_, device="cuda")
+            ws_ = B.alloc_workspace(B.s4c_draft_linear_workspace_size(Tn, Hd, Hd))
+            t_dl = best(lambda: B.s4c_draft_linear(e_, f_, W_, o_, b_, ws_))
+            t_lib = best(lambda: torch.addmm(b_, torch.cat([e_, f_], 1), W_.t()))
+            fl = 2.0 * Tn * 2 * Hd * Hd
+            w_bytes = 2.0 * Hd * Hd * W_.element_size()
+            rec["draft_linear"].append({"tokens": Tn, "hidden": Hd, "ms": t_dl, "TFLOPs": fl / t_dl / 1e9,
+                                        "frac_of_mfma_peak": fl / t_dl / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                        "W_GBps": w_bytes / t_dl / 1e6, "W_frac_of_hbm_peak": w_bytes / t_dl / 1e6 / HBM_PEAK_GBPS,
+                                        "torch_cat_addmm_ms": t_lib, "torch_TFLOPs": fl / t_lib / 1e9})
+            del e_, f_, o_, ws_
+        del W_
     if args.build_tree:
         d = copies[0]
         nchild = torch.zeros(cfg.B, cfg.N, dtype=torch.int32, device="cuda")

@@ -21,7 +21,7 @@ S4C_SEQ_BAD_TREE, S4C_SEQ_BAD_LEN, S4C_SEQ_TIMEOUT = 1, 2, 4
 EXPORTS = ("s4c_tree_attn_workspace_size", "s4c_tree_attn", "s4c_accept_path_workspace_size",
            "s4c_accept_path", "s4c_kv_compact", "s4c_strerror", "s4c_tree_attn_num_splits",
            "s4c_accept_resample", "s4c_accept_resample_workspace_size", "s4c_commit_path", "s4c_build_tree", "s4c_build_tree_workspace_size",
-           "s4c_draft_linear", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged", "s4c_accept_path_static")
+           "s4c_draft_linear", "s4c_draft_linear_workspace_size", "s4c_tree_attn_paged", "s4c_kv_compact_paged", "s4c_commit_path_paged", "s4c_accept_path_static")
 
 
 class S4CError(RuntimeError):
@@ -83,7 +83,9 @@ def lib() -> C.CDLL:
         L.s4c_kv_compact_paged.argtypes = [C.POINTER(AttnShape)] + [C.c_void_p] * 5 + [C.c_int32] * 3 + [C.c_void_p] * 3 + [
             C.c_int32] + [C.c_void_p] * 3
         L.s4c_draft_linear.restype = C.c_int
-        L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6
+        L.s4c_draft_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        L.s4c_draft_linear_workspace_size.restype = C.c_size_t
+        L.s4c_draft_linear_workspace_size.argtypes = [C.c_int32] * 3
         L.s4c_accept_path_static.restype = C.c_int
         L.s4c_accept_path_static.argtypes = [C.c_int32] * 5 + [C.c_float] + [C.c_void_p] * 5 + [C.c_int32] + [
             C.c_void_p] * 6
@@ -366,8 +368,13 @@ def s4c_build_tree(draft_logits, nchild, root_token, kmax: int, parent, tokens, 
                                 _ptr(level), _ptr(status), _ptr(workspace), ws_bytes, _stream()))
 
 
-def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
-    """out[t] = W @ concat(e[t], f[t]) + bias (bf16 or fp16, fp32 accumulate); returns ``out``."""
+def s4c_draft_linear_workspace_size(T: int, H: int, Hout: int) -> int:
+    return int(lib().s4c_draft_linear_workspace_size(T, H, Hout))
+
+
+def s4c_draft_linear(e, f, W, out, bias=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[t] = W @ concat(e[t], f[t]) + bias (bf16 or fp16, fp32 accumulate); returns ``out``.  Up to 128 tokens
+    the call needs ``workspace`` (s4c_draft_linear_workspace_size bytes)."""
     T, H = e.shape
     Hout = W.shape[0]
     if tuple(f.shape) != (T, H) or tuple(W.shape) != (Hout, 2 * H) or tuple(out.shape) != (T, Hout):
@@ -377,7 +384,9 @@ def s4c_draft_linear(e, f, W, out, bias=None) -> torch.Tensor:
     for t in (e, f, W, out) + ((bias,) if bias is not None else ()):
         if t.dtype != e.dtype or e.dtype not in (torch.bfloat16, torch.float16):
             raise TypeError("s4c_draft_linear takes bfloat16 or float16 tensors of one type")
-    _check(lib().s4c_draft_linear(T, H, Hout, _dtype_code(e), _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out), _stream()))
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().s4c_draft_linear(T, H, Hout, _dtype_code(e), _ptr(e), _ptr(f), _ptr(W), _ptr(bias), _ptr(out),
+                                  _ptr(workspace), ws_bytes, _stream()))
     return out
 
 

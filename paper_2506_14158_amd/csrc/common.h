@@ -198,10 +198,15 @@ struct LinearArgs {
     const void* W;       // [Hout][2H]
     const void* bias;    // [Hout] or null
     void* out;           // [T][Hout]
+    float* ws;           // few-token path: [nslices][T][Hout] partial sums
     int32_t T, H, Hout, dtype;
     int32_t ttiles, otiles;   // set by the launcher
+    int32_t ksub, kslice, nslices;   // few-token path: reduction elements per LDS fill, per workgroup, workgroups per tile
 };
 hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st);
+hipError_t launch_draft_linear_small(const LinearArgs& a, hipStream_t st);   // T <= draft_linear_small_max_tokens()
+int draft_linear_small_max_tokens();
+void draft_linear_small_plan(int T, int H, int Hout, int cus, int* ksub, int* kslice, int* nslices);
 int draft_linear_tile_out();
 int draft_linear_tile_k();
 

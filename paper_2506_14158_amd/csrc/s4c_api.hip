@@ -537,8 +537,18 @@ s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, co
                        path, accept_len, max_path, features, feature_bytes, features_out, dst_index, status, hip_stream);
 }
 
+size_t s4c_draft_linear_workspace_size(int32_t T, int32_t H, int32_t Hout) {
+    if (T <= 0 || H <= 0 || Hout <= 0 || T > draft_linear_small_max_tokens() || H % draft_linear_tile_k() != 0 ||
+        Hout % draft_linear_tile_out() != 0)
+        return 0;
+    int ksub, kslice, nslices;
+    draft_linear_small_plan(T, H, Hout, device_cus(), &ksub, &kslice, &nslices);
+    return (((size_t)nslices * T * Hout * sizeof(float) + 255) / 256) * 256;
+}
+
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
-                            const void* W, const void* bias, void* out, void* hip_stream) {
+                            const void* W, const void* bias, void* out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
     if (!e || !f || !W || !out) return S4C_ERR_NULL;
     if (T <= 0 || H <= 0 || Hout <= 0) return S4C_ERR_SHAPE;
     if ((dtype != S4C_BF16 && dtype != S4C_F16) || H % draft_linear_tile_k() != 0 || Hout % draft_linear_tile_out() != 0 ||
@@ -546,7 +556,16 @@ s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, c
         return S4C_ERR_UNSUPPORTED;
     if ((((uintptr_t)e) | ((uintptr_t)f) | ((uintptr_t)W) | ((uintptr_t)out)) & 15) return S4C_ERR_SHAPE;
     LinearArgs a;
-    a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.T = T; a.H = H; a.Hout = Hout; a.dtype = dtype; a.ttiles = a.otiles = 0;
+    a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.ws = nullptr; a.T = T; a.H = H; a.Hout = Hout; a.dtype = dtype;
+    a.ttiles = a.otiles = 0; a.ksub = a.kslice = a.nslices = 0;
+    if (T <= draft_linear_small_max_tokens()) {
+        // few tokens: the weight-streaming kernel with split-K partial sums in the workspace
+        const size_t need = s4c_draft_linear_workspace_size(T, H, Hout);
+        if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
+        draft_linear_small_plan(T, H, Hout, device_cus(), &a.ksub, &a.kslice, &a.nslices);
+        a.ws = (float*)workspace;
+        return launch_draft_linear_small(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+    }
     return launch_draft_linear(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }
 

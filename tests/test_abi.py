@@ -119,9 +119,15 @@ def test_paged_and_multi_layer_host_errors(L):
     cmp_ = lambda bt=one, ps=128, mb=64, npg=200, layers=4: L.s4c_commit_path_paged(
         C.byref(s), layers, one, one, one, one, bt, mb, ps, npg, one, one, one, 4, None, 0, None, None, None, None)
     assert cmp_(bt=None) == -1 and cmp_(ps=48) == -3 and cmp_(mb=0) == -2 and cmp_(layers=0) == -2
-    dl = lambda T=64, H=64, Hout=256, dt=1, e=one: L.s4c_draft_linear(T, H, Hout, dt, e, one, one, None, one, None)
+    dl = lambda T=300, H=64, Hout=256, dt=1, e=one, ws=None, wsb=0: L.s4c_draft_linear(T, H, Hout, dt, e, one, one, None, one,
+                                                                                         ws, wsb, None)
     assert dl(e=None) == -1 and dl(T=0) == -2 and dl(dt=0) == -3 and dl(H=40) == -3 and dl(Hout=100) == -3
     assert dl(e=C.c_void_p(8)) == -2                          # 16-byte alignment
+    # up to 128 tokens the call streams W with split-K partial sums in a workspace
+    assert B.s4c_draft_linear_workspace_size(300, 64, 256) == 0
+    need = B.s4c_draft_linear_workspace_size(60, 4096, 4096)
+    assert need >= 60 * 4096 * 4 and need % 256 == 0
+    assert dl(T=60, H=4096, Hout=4096) == -4 and dl(T=60, H=4096, Hout=4096, ws=one, wsb=need - 1) == -4
 
 
 def test_missing_library_fails_loudly(monkeypatch):

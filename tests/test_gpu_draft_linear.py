@@ -23,7 +23,10 @@ def make(T, H, Hout, seed, bias=True):
 
 def run(e, f, W, b):
     out = torch.full((e.shape[0], W.shape[0]), float("nan"), dtype=torch.bfloat16, device="cuda")
-    B.s4c_draft_linear(np_to_torch(e), np_to_torch(f), np_to_torch(W), out, None if b is None else np_to_torch(b))
+    ws = B.alloc_workspace(B.s4c_draft_linear_workspace_size(e.shape[0], e.shape[1], W.shape[0]))
+    if ws is not None:
+        ws.view(torch.float32).fill_(float("nan"))       # partial sums are written before they are read
+    B.s4c_draft_linear(np_to_torch(e), np_to_torch(f), np_to_torch(W), out, None if b is None else np_to_torch(b), ws)
     torch.cuda.synchronize()
     return out.float().cpu().numpy().astype(np.float64)
 
@@ -39,6 +42,29 @@ def close(g, o):
 def test_element_by_element(T, H, Hout, bias):
     e, f, W, b = make(T, H, Hout, T + H, bias)
     close(run(e, f, W, b), O.draft_linear(e, f, W, b))
+
+
+@pytest.mark.parametrize("T,H,Hout,bias", [(1, 4096, 4096, True), (15, 4096, 4096, False), (60, 4096, 4096, True),
+                                           (128, 4096, 4096, True), (60, 5120, 5120, True), (33, 96, 256, True),
+                                           (128, 32, 512, False), (17, 1056, 768, True), (100, 8192, 1024, True)])
+def test_few_tokens_element_by_element(T, H, Hout, bias):
+    """Up to 128 tokens (a draft tree at batch 1; 4096 / 5120 are the hidden sizes of Vicuna 7B / 13B): the
+    weight-streaming kernel with split-K, every output element against the oracle."""
+    e, f, W, b = make(T, H, Hout, 1000 + T + H, bias)
+    close(run(e, f, W, b), O.draft_linear(e, f, W, b))
+
+
+def test_few_tokens_selector_weights_are_exact_and_deterministic():
+    T, H = 60, 512
+    e, f, _, _ = make(T, H, H, 5)
+    one = synth.f32_to_bf16_bits(np.eye(H, dtype=np.float32))
+    zero = np.zeros((H, H), dtype=np.uint16)
+    assert np.array_equal(run(e, f, np.ascontiguousarray(np.hstack([one, zero])), None), synth.bf16_bits_to_f32(e).astype(np.float64))
+    assert np.array_equal(run(e, f, np.ascontiguousarray(np.hstack([zero, one])), None), synth.bf16_bits_to_f32(f).astype(np.float64))
+    e, f, W, b = make(60, 4096, 4096, 8)
+    first = run(e, f, W, b)
+    for _ in range(3):
+        assert np.array_equal(run(e, f, W, b), first)
 
 
 def test_selector_weights_are_exact():
@@ -72,5 +98,7 @@ def test_rejects_unsupported_shapes():
         B.s4c_draft_linear(t(4, 64), t(4, 64), t(100, 128), t(4, 100))
     with pytest.raises(B.S4CError):       # H must be a multiple of 32
         B.s4c_draft_linear(t(4, 40), t(4, 40), t(256, 80), t(4, 256))
+    with pytest.raises(B.S4CError):       # few tokens: the workspace is required
+        B.s4c_draft_linear(t(4, 64), t(4, 64), t(256, 128), t(4, 256))
     with pytest.raises(TypeError):
         B.s4c_draft_linear(t(4, 64).float(), t(4, 64).float(), t(256, 128).float(), t(4, 256).float())

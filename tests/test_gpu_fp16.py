@@ -151,7 +151,8 @@ def test_draft_linear(T, H, Hout, bias):
     W = h(rng.standard_normal((Hout, 2 * H)) / np.sqrt(2 * H))
     b = h(rng.standard_normal(Hout)) if bias else None
     out = torch.full((T, Hout), float("nan"), dtype=torch.float16, device="cuda")
-    B.s4c_draft_linear(np_to_torch(e), np_to_torch(f_), np_to_torch(W), out, None if b is None else np_to_torch(b))
+    B.s4c_draft_linear(np_to_torch(e), np_to_torch(f_), np_to_torch(W), out, None if b is None else np_to_torch(b),
+                       B.alloc_workspace(B.s4c_draft_linear_workspace_size(e.shape[0], e.shape[1], W.shape[0])))
     torch.cuda.synchronize()
     g = out.float().cpu().numpy().astype(np.float64)
     o = O.draft_linear(e, f_, W, b)

@@ -38,6 +38,10 @@ def test_drafter_side_calls_replay_from_a_hip_graph():
     e, f = (torch.randn(T, H, device="cuda", generator=g).bfloat16() for _ in range(2))
     W = (torch.randn(H, 2 * H, device="cuda", generator=g) / (2 * H) ** 0.5).bfloat16()
     h_out = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+    dl_ws = B.alloc_workspace(B.s4c_draft_linear_workspace_size(T, H, H))      # None above 128 tokens
+    # the same projection on one sequence's tokens (<= 128: the weight-streaming kernel and its workspace)
+    h_small = torch.empty(N, H, dtype=torch.bfloat16, device="cuda")
+    dl_ws_small = B.alloc_workspace(B.s4c_draft_linear_workspace_size(N, H, H))
     # commit: 3 layers + feature rows
     Ly, Hkv, D, P = 3, 2, 128, 100
     S_cap = P + levels
@@ -52,19 +56,20 @@ def test_drafter_side_calls_replay_from_a_hip_graph():
 
     def calls():
         B.s4c_build_tree(dl, nchild, root, kmax, o_par, o_tok, o_pd, bt_ws, cfg.temperature)
-        B.s4c_draft_linear(e, f, W, h_out)
+        B.s4c_draft_linear(e, f, W, h_out, None, dl_ws)
+        B.s4c_draft_linear(e[:N], f[:N], W, h_small, None, dl_ws_small)
         tv.accept_resample(d["logits"], d["draft_probs"], d["parent"], d["tokens"], d["uniforms"], d["u_resample"],
                            cfg.temperature)
         tv.commit_path(kt, vt, kc, vc, cl, feats, fout)
 
-    outs = lambda: (o_par, o_tok, o_pd, h_out, tv.path, tv.accept_len, tv.bonus_token, kc, vc, cl, fout)
+    outs = lambda: (o_par, o_tok, o_pd, h_out, h_small, tv.path, tv.accept_len, tv.bonus_token, kc, vc, cl, fout)
     bits = lambda t: t.view(torch.int16) if t.dtype == torch.bfloat16 else t
 
     def reset():
         kc.copy_(kc0); vc.copy_(vc0); cl.copy_(cl0)
         for t in (o_par, o_tok, tv.path, tv.accept_len, tv.bonus_token):
             t.fill_(-9)
-        o_pd.fill_(-1.0); h_out.zero_(); fout.zero_()
+        o_pd.fill_(-1.0); h_out.zero_(); h_small.zero_(); fout.zero_()
 
     calls()                                  # eager once: allocates the verifier's slot workspace, gives the reference
     torch.cuda.synchronize()
