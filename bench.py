@@ -80,14 +80,18 @@ def _timed_ms(torch, fn, reps=10):
     return e0.elapsed_time(e1) / reps
 
 
-def csrc_digest():
-    """Digest of the library's sources: a committed HBM-traffic figure is only quoted for the kernels it was
-    measured on."""
+ATTN_SOURCES = ("tree_attn_mfma.hip", "tree_attn_mfma_smallm.hip", "tree_attn_generic.hip", "mfma_common.h", "common.h", "s4c_api.hip")
+
+
+def csrc_digest(names=None):
+    """Digest of the library's sources (all of them, or the named files of csrc/ plus the public header): a
+    committed HBM-traffic figure is only quoted for the kernels it was measured on."""
     import glob
     import hashlib
     h = hashlib.sha256()
-    files = sorted(glob.glob(os.path.join(ROOT, "paper_2506_14158_amd", "csrc", "*.h*"))) + [os.path.join(ROOT, "include", "s4c.h")]
-    for f in files:
+    csrc = os.path.join(ROOT, "paper_2506_14158_amd", "csrc")
+    files = sorted(glob.glob(os.path.join(csrc, "*.h*"))) if names is None else [os.path.join(csrc, n) for n in names]
+    for f in files + [os.path.join(ROOT, "include", "s4c.h")]:
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
@@ -95,12 +99,12 @@ def csrc_digest():
 
 def committed_traffic(cfg_index):
     """HBM bytes per s4c_tree_attn call from the committed rocprofv3 --pmc summary (profiles/traffic.json), or
-    None if there is none for this config or it was taken on other kernel sources."""
+    None if there is none for this config or it was taken on other sources of the attention kernels and their planner."""
     try:
         tr = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get("cfg%d" % cfg_index)
     except (OSError, ValueError):
         return None
-    if not tr or tr.get("csrc_sha16") != csrc_digest():
+    if not tr or tr.get("attn_src_sha16") != csrc_digest(ATTN_SOURCES):
         return None
     return tr
 
@@ -309,6 +313,7 @@ def main():
         "phases_ms": {"tree_attn": t_attn * 1e3, "accept_path": t_acc * 1e3, "kv_compact": t_cmp * 1e3},
         "accept_path_GBps": acc_roof["achieved"], "accept_rows_scanned": acc_roof["rows_scanned"],
         "csrc_sha16": csrc_digest(),
+        "attn_src_sha16": csrc_digest(ATTN_SOURCES),
         "timing_note": "ms_per_step and value: wall clock around the K timed steps; ms_median / ms_min and every phase: "
                        "HIP events on the launch stream",
         "paper_context": "paper reports 2.26x-2.60x end-to-end vs autoregressive decoding (A100-40GB / 4xRTX4090, fp16, batch 1)",
