@@ -283,11 +283,12 @@ s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, co
  *   H a multiple of 32 (<= 16384), Hout a multiple of 256, T*H < 2^30; all pointers 16-byte
  *   aligned device pointers.
  *   workspace  >= s4c_draft_linear_workspace_size(T, H, Hout) bytes, 256-byte aligned, contents need
- *              not be initialised; that size is 0 (and the pointer may be NULL) for T > 128.  Up to
- *              128 tokens -- a draft tree at batch 1, the operating point of Sec. 4.1.2 -- the op
- *              is a stream over W, split over the reduction dimension to fill the chip, and the
- *              workspace holds the slices' fp32 partial sums (added in a fixed order: results are
- *              deterministic). */
+ *              not be initialised; that size is 0 (and the pointer may be NULL) for T > 512.  Up to
+ *              512 tokens the op is a stream over W: it runs in passes of at most 128 tokens -- one
+ *              pass for a draft tree at batch 1, the operating point of Sec. 4.1.2 -- each split
+ *              over the reduction dimension to fill the chip, and the workspace holds the slices'
+ *              fp32 partial sums (added in a fixed order: results are deterministic).  S4C_ERR_WORKSPACE
+ *              if it is missing, too small or misaligned. */
 size_t s4c_draft_linear_workspace_size(int32_t T, int32_t H, int32_t Hout);
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
                             const void* W, const void* bias, void* out, void* workspace, size_t workspace_bytes,

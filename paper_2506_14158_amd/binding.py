@@ -373,7 +373,7 @@ def s4c_draft_linear_workspace_size(T: int, H: int, Hout: int) -> int:
 
 
 def s4c_draft_linear(e, f, W, out, bias=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """out[t] = W @ concat(e[t], f[t]) + bias (bf16 or fp16, fp32 accumulate); returns ``out``.  Up to 128 tokens
+    """out[t] = W @ concat(e[t], f[t]) + bias (bf16 or fp16, fp32 accumulate); returns ``out``.  Up to 512 tokens
     the call needs ``workspace`` (s4c_draft_linear_workspace_size bytes)."""
     T, H = e.shape
     Hout = W.shape[0]

@@ -205,7 +205,8 @@ struct LinearArgs {
 };
 hipError_t launch_draft_linear(const LinearArgs& a, hipStream_t st);
 hipError_t launch_draft_linear_small(const LinearArgs& a, hipStream_t st);   // T <= draft_linear_small_max_tokens()
-int draft_linear_small_max_tokens();
+int draft_linear_small_max_tokens();      // tokens per launch of the weight-streaming kernel
+int draft_linear_stream_max_tokens();     // token count up to which the entry point uses it (in passes)
 void draft_linear_small_plan(int T, int H, int Hout, int cus, int* ksub, int* kslice, int* nslices);
 int draft_linear_tile_out();
 int draft_linear_tile_k();

@@ -33,7 +33,10 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kStepK = 128;             // reduction elements per step (4 MFMAs per token block)
 constexpr int kMaxT = 128;
-constexpr int kLdsX = 64 * 1024;        // LDS for the x sub-slice (128 KB measured the same at 60 tokens)
+#ifndef S4C_DL_STREAM_MAX
+#define S4C_DL_STREAM_MAX 512
+#endif
+constexpr int kLdsX = 128 * 1024;       // LDS for the x sub-slice: a CU holds one workgroup, so it may take most of the 160 KB
 constexpr int kPadB = 16;               // row padding: 16 tokens x 16-byte reads hit 16 different bank groups
 
 // reduction elements of x that fit in LDS at a time for this token count: whole steps
@@ -192,6 +195,7 @@ hipError_t launch_small_by_tokens(const LinearArgs& a, hipStream_t st) {
 }  // namespace
 
 int draft_linear_small_max_tokens() { return kMaxT; }
+int draft_linear_stream_max_tokens() { return S4C_DL_STREAM_MAX; }
 
 // The split of the reduction dimension for this shape (a fixed function of the sizes and the CU count): as
 // many slices as give every CU at most one workgroup, each a whole number of equal sub-slices that fit in LDS.

@@ -538,12 +538,21 @@ s4c_status s4c_commit_path_paged(const s4c_attn_shape* shape, int32_t layers, co
 }
 
 size_t s4c_draft_linear_workspace_size(int32_t T, int32_t H, int32_t Hout) {
-    if (T <= 0 || H <= 0 || Hout <= 0 || T > draft_linear_small_max_tokens() || H % draft_linear_tile_k() != 0 ||
+    if (T <= 0 || H <= 0 || Hout <= 0 || T > draft_linear_stream_max_tokens() || H % draft_linear_tile_k() != 0 ||
         Hout % draft_linear_tile_out() != 0)
         return 0;
-    int ksub, kslice, nslices;
-    draft_linear_small_plan(T, H, Hout, device_cus(), &ksub, &kslice, &nslices);
-    return (((size_t)nslices * T * Hout * sizeof(float) + 255) / 256) * 256;
+    // the largest need of any pass (passes as in s4c_draft_linear: equal sizes, the last one may be shorter)
+    const int step = draft_linear_small_max_tokens();
+    const int passes = (T + step - 1) / step, per = (T + passes - 1) / passes;
+    size_t need = 0;
+    for (int t0 = 0; t0 < T; t0 += per) {
+        const int Tp = T - t0 < per ? T - t0 : per;
+        int ksub, kslice, nslices;
+        draft_linear_small_plan(Tp, H, Hout, device_cus(), &ksub, &kslice, &nslices);
+        const size_t b = (size_t)nslices * Tp * Hout * sizeof(float);
+        if (b > need) need = b;
+    }
+    return ((need + 255) / 256) * 256;
 }
 
 s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, const void* e, const void* f,
@@ -558,13 +567,25 @@ s4c_status s4c_draft_linear(int32_t T, int32_t H, int32_t Hout, int32_t dtype, c
     LinearArgs a;
     a.e = e; a.f = f; a.W = W; a.bias = bias; a.out = out; a.ws = nullptr; a.T = T; a.H = H; a.Hout = Hout; a.dtype = dtype;
     a.ttiles = a.otiles = 0; a.ksub = a.kslice = a.nslices = 0;
-    if (T <= draft_linear_small_max_tokens()) {
-        // few tokens: the weight-streaming kernel with split-K partial sums in the workspace
+    if (T <= draft_linear_stream_max_tokens()) {
+        // few tokens: the weight-streaming kernel with split-K partial sums in the workspace, in passes of at most
+        // 128 tokens (each pass streams W once; up to four passes still beat the tiled kernel, which has no split-K
+        // and fills few workgroups at these sizes)
         const size_t need = s4c_draft_linear_workspace_size(T, H, Hout);
         if (!workspace || workspace_bytes < need || (((uintptr_t)workspace) & 255)) return S4C_ERR_WORKSPACE;
-        draft_linear_small_plan(T, H, Hout, device_cus(), &a.ksub, &a.kslice, &a.nslices);
+        const int step = draft_linear_small_max_tokens();
+        const int passes = (T + step - 1) / step, per = (T + passes - 1) / passes;      // equal passes
         a.ws = (float*)workspace;
-        return launch_draft_linear_small(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
+        for (int t0 = 0; t0 < T; t0 += per) {
+            LinearArgs p = a;
+            p.T = T - t0 < per ? T - t0 : per;
+            p.e = (const char*)e + (size_t)t0 * H * 2;
+            p.f = (const char*)f + (size_t)t0 * H * 2;
+            p.out = (char*)out + (size_t)t0 * Hout * 2;
+            draft_linear_small_plan(p.T, H, Hout, device_cus(), &p.ksub, &p.kslice, &p.nslices);
+            if (launch_draft_linear_small(p, (hipStream_t)hip_stream) != hipSuccess) return S4C_ERR_HIP;
+        }
+        return S4C_OK;
     }
     return launch_draft_linear(a, (hipStream_t)hip_stream) == hipSuccess ? S4C_OK : S4C_ERR_HIP;
 }

@@ -123,8 +123,9 @@ def test_paged_and_multi_layer_host_errors(L):
                                                                                          ws, wsb, None)
     assert dl(e=None) == -1 and dl(T=0) == -2 and dl(dt=0) == -3 and dl(H=40) == -3 and dl(Hout=100) == -3
     assert dl(e=C.c_void_p(8)) == -2                          # 16-byte alignment
-    # up to 128 tokens the call streams W with split-K partial sums in a workspace
-    assert B.s4c_draft_linear_workspace_size(300, 64, 256) == 0
+    # up to 512 tokens the call streams W (passes of at most 128 tokens) with split-K partial sums in a workspace
+    assert B.s4c_draft_linear_workspace_size(600, 64, 256) == 0 and dl(T=600, e=C.c_void_p(16)) != -4
+    assert B.s4c_draft_linear_workspace_size(300, 64, 256) >= 100 * 256 * 4 and dl(T=300) == -4
     need = B.s4c_draft_linear_workspace_size(60, 4096, 4096)
     assert need >= 60 * 4096 * 4 and need % 256 == 0
     assert dl(T=60, H=4096, Hout=4096) == -4 and dl(T=60, H=4096, Hout=4096, ws=one, wsb=need - 1) == -4

@@ -54,6 +54,14 @@ def test_few_tokens_element_by_element(T, H, Hout, bias):
     close(run(e, f, W, b), O.draft_linear(e, f, W, b))
 
 
+@pytest.mark.parametrize("T,H,Hout", [(256, 5120, 5120), (200, 4096, 4096), (512, 1024, 512), (513, 1024, 512), (129, 96, 256)])
+def test_a_few_hundred_tokens_run_in_passes(T, H, Hout):
+    """129 .. 512 tokens (config 3's four trees are 256): the weight-streaming kernel in equal passes of at most
+    128 tokens, the last one possibly shorter; 513 tokens is the first size of the tiled kernel."""
+    e, f, W, b = make(T, H, Hout, 2000 + T + H, True)
+    close(run(e, f, W, b), O.draft_linear(e, f, W, b))
+
+
 def test_few_tokens_selector_weights_are_exact_and_deterministic():
     T, H = 60, 512
     e, f, _, _ = make(T, H, H, 5)
