@@ -80,31 +80,32 @@ def _timed_ms(torch, fn, reps=10):
     return e0.elapsed_time(e1) / reps
 
 
-ATTN_SOURCES = ("tree_attn_mfma.hip", "tree_attn_mfma_smallm.hip", "tree_attn_generic.hip", "mfma_common.h", "common.h", "s4c_api.hip")
+ATTN_SOURCES = ("tree_attn_mfma.hip", "tree_attn_mfma_smallm.hip", "tree_attn_generic.hip", "mfma_common.h")
 
 
 def csrc_digest(names=None):
-    """Digest of the library's sources (all of them, or the named files of csrc/ plus the public header): a
+    """Digest of the library's sources (all of them with the public header, or the named files of csrc/): a
     committed HBM-traffic figure is only quoted for the kernels it was measured on."""
     import glob
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2506_14158_amd", "csrc")
     files = sorted(glob.glob(os.path.join(csrc, "*.h*"))) if names is None else [os.path.join(csrc, n) for n in names]
-    for f in files + [os.path.join(ROOT, "include", "s4c.h")]:
+    for f in files + ([os.path.join(ROOT, "include", "s4c.h")] if names is None else []):
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
 
 
-def committed_traffic(cfg_index):
+def committed_traffic(cfg_index, kv_splits):
     """HBM bytes per s4c_tree_attn call from the committed rocprofv3 --pmc summary (profiles/traffic.json), or
-    None if there is none for this config or it was taken on other sources of the attention kernels and their planner."""
+    None if there is none for this config or it was taken on other sources of the attention kernels or with another
+    number of KV splits (the planner's choice)."""
     try:
         tr = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get("cfg%d" % cfg_index)
     except (OSError, ValueError):
         return None
-    if not tr or tr.get("attn_src_sha16") != csrc_digest(ATTN_SOURCES):
+    if not tr or tr.get("attn_src_sha16") != csrc_digest(ATTN_SOURCES) or tr.get("kv_splits") != kv_splits:
         return None
     return tr
 
@@ -193,8 +194,9 @@ def rooflines(w, t):
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["frac_of_hbm_peak_kv_read"] = hbm_frac
     roof["frac_of_mfma_peak"] = mfma_frac
-    tr = committed_traffic(cfg.index)
+    tr = committed_traffic(cfg.index, tv.num_splits)
     roof["traffic"] = (tr["fetch_bytes"] + tr["write_bytes"]) if tr else None
+    roof["traffic_source"] = ("%s, commit %s" % (tr["source"], tr["taken_at_commit"])) if tr else None
     roof["traffic_over_algorithmic"] = (roof["traffic"] / float(kv_bytes + qo_bytes)) if tr else None
     roof["kernel"] = "s4c_tree_attn (%d KV split%s)" % (tv.num_splits, "" if tv.num_splits == 1 else "s")
     roof["ms"] = t_attn * 1e3
