@@ -232,7 +232,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="1..5 (the five benchmark configs); 5 is the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
-                    help="skip the `configs` array (the other four configs timed the same way, a few seconds each)")
+                    help="only the selected config's step: skip the `configs` array (the other four configs timed the same "
+                         "way, a few seconds each) and the legs of the other entry points that a plain run adds "
+                         "(accept_resample, build_tree, draft_linear, multi_layer with 2 layers)")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured-ceiling probes (measured_peaks)")
     ap.add_argument("--warm", action="store_true", help="re-use one input copy every step (cache-warm numbers)")
     ap.add_argument("--resample", action="store_true",
@@ -262,6 +264,10 @@ def main():
                     help="also time s4c_tree_attn with every Q/K/V element set to 0.5 (same launches, same instruction "
                          "stream; reported as attn_constant_data: shows how much of the time is the data-dependent clock)")
     args = ap.parse_args()
+    if not args.no_other_configs:
+        # the full line also times the entry points outside the three-call step, on the selected config
+        args.resample = args.build_tree = args.draft_linear = True
+        args.layers = args.layers or 2
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the step has no cross-GPU part); use --gpus 1", file=sys.stderr)
         sys.exit(2)
