@@ -1,12 +1,13 @@
 // Candidate-tree construction from the drafter's logits (paper Sec. 3.2: the top-1 continuation
 // is drafted first, the next most probable tokens are placed beside it as alternatives).
 //
-// Kernel 1 (topk_chunk): the HBM-bound part, one workgroup per (row, 8192-logit chunk) of the
-// rows that have children; a workgroup walks a segment of consecutive chunks, the next one in
-// flight while the current one is searched.  Every wavefront takes the nchild[row] largest of its
-// own 2048 logits of the chunk (wavefront maximum, ties to the lowest token id; only the lane that
-// owned a winner rescans its registers) and writes them out next to the maximum and the sum of
-// exponentials of its part: no barrier, no workgroup-level step.
+// Kernel 1 (topk_chunk): the HBM-bound part, over the rows that have children; a workgroup walks a
+// segment of consecutive 8192-logit chunks of one row, the next chunk in flight while the current
+// one is searched.  Every wavefront keeps the nchild[row] largest logits of its quarter of the
+// segment as a running sorted list (a chunk is only searched where a vote finds something above the
+// list's last entry; ties to the lowest token id) and writes the list out at the end, next to the
+// maximum and the sum of exponentials of its part: no barrier, no workgroup-level step, no
+// cross-lane step per chunk unless the list changes.
 // Kernel 2 (topk_row): one wavefront per row merges the parts' candidates into the row's top
 // nchild tokens and turns their logits into probabilities.
 // Kernel 3 (layout): one workgroup per sequence numbers the nodes level by level from the child
@@ -61,6 +62,11 @@ __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(BuildArgs a) {
     };
     bool have = ch0 < ch1 && whole(ch0);
     if (have) fetch(ch0);
+    float m_e = -INFINITY, s_e = 0.f;                  // this thread's running maximum and sum of exponentials
+    float lv[kK];                                      // the wavefront's list (uniform across lanes)
+    int32_t li[kK];
+#pragma unroll
+    for (int e = 0; e < kK; ++e) { lv[e] = (e >= kK - nc) ? -INFINITY : INFINITY; li[e] = -1; }
   for (int ch = ch0; ch < ch1; ++ch) {
     float x[kPerThread];
     int32_t idx0[NV];
@@ -85,36 +91,35 @@ __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(BuildArgs a) {
     have = ch + 1 < ch1 && whole(ch + 1);
     if (have) fetch(ch + 1);                           // in flight while this chunk is searched
 
-    // Every wave takes the nc largest of its own 2048 logits (its quarter of the chunk), one at a time, and
-    // writes them out itself: the scan has no barrier and no workgroup-level step at all.  The lanes
-    // keep only the VALUE of their largest remaining logit; a round is a wavefront maximum of those, after
-    // which the lanes that hold that value (nearly always one) look up the lowest token id that attains it
-    // in their registers, the lowest of those wins (ties to the lowest token id), and its owner removes it
-    // and recomputes its maximum.  The chunk's sum of exponentials is taken per wave against the wave's own
-    // maximum.
-    auto lane_max = [&]() {
-        float m = x[0];
+    // this thread's share of the sum of exponentials, relative to its own running maximum (rescaled when that
+    // grows): no cross-lane step per chunk
+    float m_c = x[0];
 #pragma unroll
-        for (int e = 1; e < kPerThread; e += 2) m = __builtin_fmaxf(__builtin_fmaxf(m, x[e]), x[(e + 1) & (kPerThread - 1)]);
-        return m;
-    };
-    float m_t = lane_max();
-    const size_t o = ((size_t)row * a.chunks + ch) * 4 + wave;      // this wave's quarter of the chunk
-    for (int r = 0; r < nc; ++r) {                       // a row needs only as many candidates as it has children
+    for (int e = 1; e < kPerThread; e += 2) m_c = __builtin_fmaxf(__builtin_fmaxf(m_c, x[e]), x[(e + 1) & (kPerThread - 1)]);
+    if (m_c > -INFINITY) {
+        const float m_new = fmaxf(m_e, m_c);
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < kPerThread; ++e) sum += fast_exp2((x[e] - m_new) * a.inv_temp_log2);   // padding: 0
+        s_e = s_e * fast_exp2((m_e - m_new) * a.inv_temp_log2) + sum;                              // first chunk: 0 * 0
+        m_e = m_new;
+    }
+
+    // Selection.  The wavefront keeps the nc largest logits it has seen in the segment so far as a sorted list
+    // (value descending, token id ascending), the same in every lane.  A chunk can only change the list where a
+    // lane holds something larger than the list's last entry, which a vote tells without any cross-lane data
+    // movement; after the segment's first chunk most chunks pass with few or no insertions.  An insertion is a
+    // wavefront maximum of the lanes' largest remaining logits, a lookup of the lowest token id that attains it
+    // (ties to the lowest id), a shift of the list, and the owner retiring the element.
+    float m_t = m_c;
+    for (int r = 0; r < nc; ++r) {                       // at most nc entries of one chunk can enter
+        const float tau = lv[kK - 1];                    // the list's last entry of the nc kept (see the shift below)
+        if (!__any(m_t > tau)) break;                    // (an equal later logit has a higher token id: it stays out)
         float wm = m_t;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
-        if (r == 0) {
-            float sum = 0.f;
-            if (wm > -INFINITY) {
-#pragma unroll
-                for (int e = 0; e < kPerThread; ++e) sum += fast_exp2((x[e] - wm) * a.inv_temp_log2);   // padding: 0
-            }
-            sum = wave_sum(sum);
-            if (lane == 0) { a.ws_max[o] = wm; a.ws_sum[o] = sum; }
-        }
         int32_t mine = 0x7FFFFFFF;                       // lowest token id of this lane that attains the wave maximum
-        if (m_t == wm && wm > -INFINITY) {
+        if (m_t == wm) {
 #pragma unroll
             for (int j = NV - 1; j >= 0; --j)
 #pragma unroll
@@ -124,34 +129,81 @@ __global__ __launch_bounds__(kThreads) void topk_chunk_kernel(BuildArgs a) {
         int32_t win = mine;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) win = min(win, __shfl_xor(win, off));
-        if (lane == 0) { a.ws_topv[o * kK + r] = wm; a.ws_topi[o * kK + r] = (win == 0x7FFFFFFF) ? -1 : win; }   // -1: part exhausted
-        if (r + 1 < nc && mine == win && win != 0x7FFFFFFF) {          // the owner removes the winner
+        // insert (wm, win): entries are kept in slots kK - nc .. kK - 1, so that the last kept entry sits in
+        // slot kK - 1 whatever nc is; everything smaller than the newcomer moves one slot down and the last drops
+        // out.  Tokens of later chunks have higher ids, so the newcomer goes behind entries of equal value.
+#pragma unroll
+        for (int e = kK - 1; e >= 1; --e) {
+            const bool moves = lv[e - 1] < wm;           // slot e takes slot e-1's entry
+            const bool lands = !moves && lv[e] < wm;     // slot e takes the newcomer
+            if (moves) { lv[e] = lv[e - 1]; li[e] = li[e - 1]; }
+            else if (lands) { lv[e] = wm; li[e] = win; }
+        }
+        if (lv[0] < wm) { lv[0] = wm; li[0] = win; }
+        if (mine == win) {                               // the owner removes the winner
 #pragma unroll
             for (int j = 0; j < NV; ++j)
 #pragma unroll
                 for (int q = 0; q < VN; ++q)
                     if (idx0[j] + q == win) x[j * VN + q] = -INFINITY;
-            m_t = lane_max();
+            m_t = x[0];
+#pragma unroll
+            for (int e = 1; e < kPerThread; e += 2) m_t = __builtin_fmaxf(__builtin_fmaxf(m_t, x[e]), x[(e + 1) & (kPerThread - 1)]);
         }
     }
   }
+    // ---- the wavefront's part of the segment: maximum, sum of exponentials against it, and its list
+    float wm = m_e;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+    float sum = (m_e > -INFINITY) ? s_e * fast_exp2((m_e - wm) * a.inv_temp_log2) : 0.f;
+    sum = wave_sum(sum);
+    const size_t o = ((size_t)row * a.nseg + sg) * 4 + wave;
+    if (lane == 0) { a.ws_max[o] = wm; a.ws_sum[o] = sum; }
+    if (lane < nc) {
+        // entry r of the list sits in slot kK - nc + r; a slot that was never filled holds -inf / -1 ("part exhausted")
+        float v = -INFINITY;
+        int32_t t = -1;
+#pragma unroll
+        for (int e = 0; e < kK; ++e)
+            if (e == kK - nc + lane) { v = lv[e]; t = li[e]; }
+        a.ws_topv[o * kK + lane] = v;
+        a.ws_topi[o * kK + lane] = t;
+    }
 }
 
 __global__ __launch_bounds__(64) void topk_row_kernel(BuildArgs a) {
     const int row = blockIdx.x, lane = threadIdx.x;
-    const int nc = a.nchild[row];
-    if (nc <= 0 || nc > a.kmax) return;
-    const int parts = a.chunks * 4;                          // a wavefront's quarter of a chunk each
+    const int parts = a.nseg * 4;                            // a wavefront's quarter of a segment of chunks each
     const size_t o = (size_t)row * parts;
+    // the child count, this lane's part statistics and (few parts) its whole list are requested together: the
+    // kernel is a chain of memory latencies, not of work
+    const bool few = parts <= 64, mine = lane < parts;
+    const int nc = a.nchild[row];
+    const float pm0 = (few && mine) ? a.ws_max[o + lane] : -INFINITY;
+    const float ps0 = (few && mine) ? a.ws_sum[o + lane] : 0.f;
+    float v[kK];
+    int32_t t[kK];
+#pragma unroll
+    for (int e = 0; e < kK; ++e) {
+        v[e] = (few && mine) ? a.ws_topv[(o + lane) * kK + e] : -INFINITY;      // (slots beyond nc hold leftovers: masked below)
+        t[e] = (few && mine) ? a.ws_topi[(o + lane) * kK + e] : -1;
+    }
+    if (nc <= 0 || nc > a.kmax) return;
     // row maximum and sum of exponentials from the parts' statistics
-    float m = -INFINITY;
-    for (int c = lane; c < parts; c += 64) m = fmaxf(m, a.ws_max[o + c]);
+    float m = pm0;
+    if (!few)
+        for (int c = lane; c < parts; c += 64) m = fmaxf(m, a.ws_max[o + c]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     float S = 0.f;
-    for (int c = lane; c < parts; c += 64) {
-        const float pm = a.ws_max[o + c];
-        if (pm > -INFINITY) S += a.ws_sum[o + c] * fast_exp2((pm - m) * a.inv_temp_log2);        // (a part beyond V is all padding)
+    if (few) {
+        if (pm0 > -INFINITY) S = ps0 * fast_exp2((pm0 - m) * a.inv_temp_log2);
+    } else {
+        for (int c = lane; c < parts; c += 64) {
+            const float pm = a.ws_max[o + c];
+            if (pm > -INFINITY) S += a.ws_sum[o + c] * fast_exp2((pm - m) * a.inv_temp_log2);    // (a part beyond V is all padding)
+        }
     }
     S = wave_sum(S);
     const float* cv = a.ws_topv + o * kK;
@@ -163,17 +215,12 @@ __global__ __launch_bounds__(64) void topk_row_kernel(BuildArgs a) {
             a.row_p[(size_t)row * kK + r] = found ? fast_exp2((best.v - m) * a.inv_temp_log2) / S : 0.f;
         }
     };
-    if (parts <= 64) {
+    if (few) {
         // Every part's candidates are a descending list of nc entries: lane p keeps part p's list in
         // registers (read once), offers its head in every round, and the lane that wins shifts its list.
-        float v[kK];
-        int32_t t[kK];
 #pragma unroll
-        for (int e = 0; e < kK; ++e) {
-            const bool there = lane < parts && e < nc;
-            v[e] = there ? cv[lane * kK + e] : -INFINITY;
-            t[e] = there ? ci[lane * kK + e] : -1;
-        }
+        for (int e = 0; e < kK; ++e)
+            if (e >= nc) { v[e] = -INFINITY; t[e] = -1; }
         for (int r = 0; r < nc; ++r) {
             const MaxIdx head = (t[0] >= 0) ? MaxIdx{v[0], t[0]} : MaxIdx{-INFINITY, 0x7FFFFFFF};
             const MaxIdx best = wave_best(head);
