@@ -98,11 +98,14 @@ AttnPlan plan_attn(const s4c_attn_shape& s, int32_t max_cache_len) {
     // Balance unit: the device's CUs (256 on an MI355X) for the matrix-core kernels (HBM- or MFMA-bound: what counts is
     // an equal share of work per CU), four workgroups per CU for the scalar kernel.  Split the prefix so that the launch fills
     // whole rounds of the CUs without paying for more partial results than that needs:
-    // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), at least 128 keys per split
+    // cost(s) = rounds * slots / workgroups * (1 + 4 % per extra split), chunks a multiple of 128 keys
     // (32, its key tile, for the scalar kernel, whose launches are latency-bound).
     const long slots = (long)device_cus() * (p.mfma ? 1 : 4);
     const long gran = p.mfma ? 128 : 32;
-    long max_splits = max_cache_len / gran;
+    // at least 256 keys per split for the matrix-core kernels: below that a split's fixed costs (prologue, partial
+    // results, its share of the merge) outweigh what the extra workgroups stream (1024 keys, 32 units: 4 splits
+    // measured 7 % faster than 8)
+    long max_splits = max_cache_len / (p.mfma ? 256 : 32);
     if (max_splits > 16) max_splits = 16;
     if (max_splits < 1) max_splits = 1;
     long splits = 1;
