@@ -13,7 +13,8 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller; `shape` structs are HOST
  *     pointers.  The library allocates nothing.  What it keeps between calls is per-GPU set-up
  *     only: which of its kernels already had their dynamic-LDS limit raised, the compute-unit
- *     count it sizes launches by, and the address of the fixed scratch of s4c_accept_path_static.
+ *     count it sizes launches by, the address of the fixed scratch of s4c_accept_path_static, and
+ *     a counter that gives every acceptance call its own tag.
  *   - Q, K, V, the caches / pools and `out` must be 16-byte aligned (checked: S4C_ERR_SHAPE);
  *     logits rows may have any alignment.  Floating-point inputs must be finite (no NaN, no
  *     infinity): the kernels are compiled without NaN handling, and a non-finite input gives an
