@@ -142,7 +142,8 @@ def test_whole_step_moves_fp16_rows_bit_for_bit():
     assert np.array_equal(bits(d["v_cache"]), vc.view(np.uint8))
 
 
-@pytest.mark.parametrize("T,H,Hout,bias", [(300, 64, 256, True), (777, 1024, 768, True), (2048, 512, 1024, False)])
+@pytest.mark.parametrize("T,H,Hout,bias", [(300, 64, 256, True), (777, 1024, 768, True), (2048, 512, 1024, False),
+                                           (60, 4096, 4096, True), (128, 1056, 768, False), (15, 96, 256, True)])
 def test_draft_linear(T, H, Hout, bias):
     """fp16 in/out, fp32 accumulate: |g - o| <= 2^-11 |o| + 3e-4 (half an ulp of the fp16 result plus the fp32 sum)."""
     rng = np.random.default_rng(T + H)
